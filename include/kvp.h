@@ -18,7 +18,10 @@
  *     bf16 path may run part of the work on an internal stream that forks from and joins back
  *     into the caller's stream inside the call; nothing outlives the join.  KVP_NO_OVERLAP=1 in
  *     the environment at kvp_load_weights time disables this.)
- *   - The library allocates no device memory: scratch comes in as `workspace`.
+ *   - Device memory: kvp_load_weights allocates the few small tables a handle owns (two rotary
+ *     tables of max_seq x head_dim / 2 float2 each, one flag word, the predictor's pointer and
+ *     layer-map tables) and kvp_free releases them.  No other call allocates or frees device
+ *     memory: all per-call scratch comes in as `workspace`.
  *   - Matrices are row-major [out_features, in_features] (y = W x), element type per
  *     kvp_config.dtype: float (KVP_DTYPE_F32) or bfloat16 (KVP_DTYPE_BF16).
  *   - Transformer block (fixed by the benchmark configurations, the paper only says
@@ -47,6 +50,9 @@ extern "C" {
 
 #define KVP_DTYPE_F32 0
 #define KVP_DTYPE_BF16 1
+
+/* Bits of the device-side flag word, read with kvp_check_flags. */
+#define KVP_FLAG_TOKEN_CLAMPED 1u  /* a token id outside [0, vocab) was clamped into range */
 
 /* Stages of the path, for kvp_run_stages. */
 #define KVP_STAGE_AUX 1u       /* auxiliary prefill -> auxiliary cache in the workspace      */
@@ -152,8 +158,11 @@ typedef struct {
  * not touched.  With one width per stack this is the plain [L][B][n_kv][T_cap][hd] array. */
 
 /* Validates the configuration, records the (borrowed) device pointers and builds the launch
- * plan.  Copies nothing large; the weights must outlive the handle.
- * Errors: KVP_ERR_NULL, KVP_ERR_BAD_CONFIG.  On error *out is set to NULL. */
+ * plan.  Copies nothing large; the weights must outlive the handle.  Allocates, on the current
+ * device, the small tables the handle owns (rotary tables, flag word, predictor pointer tables:
+ * a few MB for max_seq = 8192) and synchronises the device once; later calls on this handle
+ * must run with the same device current.
+ * Errors: KVP_ERR_NULL, KVP_ERR_BAD_CONFIG, KVP_ERR_HIP.  On error *out is set to NULL. */
 int kvp_load_weights(const kvp_config* cfg, const kvp_weights* weights, kvp_handle** out);
 
 /* Bytes of device scratch kvp_prefill_predict needs for a B x T prompt batch (auxiliary cache,
@@ -164,7 +173,9 @@ int kvp_load_weights(const kvp_config* cfg, const kvp_weights* weights, kvp_hand
 size_t kvp_workspace_bytes(const kvp_handle* h, int32_t B, int32_t T);
 
 /* The whole path (Algorithm "KV Prediction Inference", statements 1-4) for B prompts of T tokens.
- *   tokens     device int32 [B, T]; ids outside [0, vocab) are clamped into range.
+ *   tokens     device int32 [B, T]; ids outside [0, vocab) are clamped into range, and the clamp is
+ *              recorded in the handle's flag word (kvp_check_flags): a range check on the host
+ *              would need the ids there, which costs a synchronisation the path avoids.
  *   k_cache,
  *   v_cache    device, element type per config, [base.n_layers][B][base.n_kv][T_cap][head_dim];
  *              receives the predicted keys / values for positions 0..T-1; slots T..T_cap-1 are
@@ -221,6 +232,16 @@ int kvp_reference_prefill(kvp_handle* h, int32_t model, const int32_t* tokens, i
                           float* logits, int32_t* argmax,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The handle's device-side flag word (KVP_FLAG_* bits, set by kernels of earlier calls on this
+ * handle; Sec. 4.1's algorithm takes token ids I as given, so an id outside the vocabulary is the
+ * caller's error, reported here instead of read out of bounds).  Copies 4 bytes to the host with
+ * a blocking copy: synchronise the stream(s) the calls were enqueued on first, or bits of work
+ * still in flight are missed.  clear != 0 resets the word after reading.  Not for use during
+ * graph capture.
+ *   flags_out  host uint32.
+ * Errors: KVP_ERR_NULL, KVP_ERR_HIP. */
+int kvp_check_flags(kvp_handle* h, uint32_t* flags_out, int32_t clear);
+
 /* One pass of the generation loop that follows the first token (Sec. 4.1 "Inference", Algorithm
  * "KV Prediction Inference": p, y <- B(y, KV)): the base model alone processes, for every sequence,
  * the token it produced last.  Unlike the first-token step it computes its OWN key and value for
@@ -232,14 +253,34 @@ int kvp_reference_prefill(kvp_handle* h, int32_t model, const int32_t* tokens, i
  *   k_cache,
  *   v_cache    as for kvp_prefill_predict; slot pos of every layer is written, 0..pos are read.
  *   logits / argmax: as for kvp_prefill_predict (the distribution of the token after position pos).
- *   workspace  >= kvp_generation_workspace_bytes(h, B, pos + 1) bytes (grows with pos: size it
- *              for the longest total length once).
+ *   workspace  >= kvp_generation_workspace_bytes(h, B, pos + 1) bytes, 256-byte aligned (the base
+ *              step's activations, split partials and logits only: a few MB; it does not shrink
+ *              as pos grows, so size it for the longest total length once).  It may be the
+ *              buffer kvp_prefill_predict used: the step then overwrites the start of what that
+ *              call left there, the auxiliary cache included.
  * Needs base.wk / base.wv (KVP_ERR_NULL if they were not given).  Caller's stream only. */
 size_t kvp_generation_workspace_bytes(const kvp_handle* h, int32_t B, int32_t T_total);
 int kvp_generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos,
                         void* k_cache, void* v_cache, int64_t T_cap,
                         float* logits, int32_t* argmax,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The workspace plan of a B x T call to kvp_prefill_predict / kvp_run_stages, for tests and
+ * tools: every region the library carves out of the workspace, in address order.  Runs entirely on
+ * the host (no device, no weights needed): the same planner the calls use, applied to `cfg`.
+ *   regions        host array of `capacity` entries, may be NULL to query the count only.
+ *   n_regions      host: number of regions of the plan (also when it exceeds capacity).
+ *   total_bytes    host: what kvp_workspace_bytes returns for this shape.
+ * A region's `bytes` is what the planner reserved; `bytes_touched` is what the kernels of such a
+ * call read or write there according to the launch-side shape rules (number of attention splits
+ * and the like).  Regions never overlap and bytes_touched <= bytes; a test checks both over a
+ * grid of shapes.  Errors: KVP_ERR_NULL, KVP_ERR_BAD_CONFIG, KVP_ERR_BAD_SHAPE. */
+typedef struct {
+  char name[24];
+  uint64_t offset, bytes, bytes_touched;
+} kvp_plan_region;
+int kvp_debug_plan(const kvp_config* cfg, int32_t B, int32_t T, kvp_plan_region* regions, int32_t capacity,
+                   int32_t* n_regions, uint64_t* total_bytes);
 
 /* Per-kernel-class timers.  While enabled, one HIP event is recorded on the caller's stream after
  * every launch (a decode-attention split + merge pair counts as one); the time between consecutive
@@ -251,7 +292,9 @@ int kvp_profile_enable(kvp_handle* h, int32_t on);
 int kvp_profile_reset(kvp_handle* h);
 int kvp_profile_read(kvp_handle* h, double* ms, int64_t* launches);
 
-/* Releases the handle (host metadata and profiling events only). NULL is allowed. */
+/* Releases the handle: host metadata, the internal stream and events, profiling events, and the
+ * device tables kvp_load_weights allocated (rotary tables, flag word, predictor pointer tables).
+ * Synchronises the internal stream first.  NULL is allowed. */
 void kvp_free(kvp_handle* h);
 
 /* Message of the last error on this thread ("" if none); storage is thread-local and static. */

@@ -19,8 +19,10 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 MODEL_BASE, MODEL_AUX = 0, 1
 EXPORTS = ("kvp_load_weights", "kvp_workspace_bytes", "kvp_prefill_predict", "kvp_run_stages",
            "kvp_aux_cache_offsets", "kvp_reference_workspace_bytes", "kvp_reference_prefill",
-           "kvp_generation_workspace_bytes", "kvp_generation_step", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
+           "kvp_generation_workspace_bytes", "kvp_generation_step", 
+           "kvp_check_flags", "kvp_debug_plan", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
            "kvp_free", "kvp_last_error", "kvp_version")
+FLAG_TOKEN_CLAMPED = 1
 
 
 class KVPError(RuntimeError):
@@ -50,6 +52,10 @@ class ModelWeights(C.Structure):
 
 class Weights(C.Structure):
     _fields_ = [("base", ModelWeights), ("aux", ModelWeights), ("pred_wk", PP), ("pred_wv", PP)]
+
+
+class PlanRegion(C.Structure):
+    _fields_ = [("name", C.c_char * 24), ("offset", C.c_uint64), ("bytes", C.c_uint64), ("bytes_touched", C.c_uint64)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -87,6 +93,11 @@ def lib() -> C.CDLL:
     L.kvp_generation_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.kvp_generation_step.restype = C.c_int
+    L.kvp_check_flags.argtypes = [C.c_void_p, C.POINTER(C.c_uint32), C.c_int32]
+    L.kvp_check_flags.restype = C.c_int
+    L.kvp_debug_plan.argtypes = [C.POINTER(Config), C.c_int32, C.c_int32, C.POINTER(PlanRegion), C.c_int32,
+                                 C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
+    L.kvp_debug_plan.restype = C.c_int
     L.kvp_aux_cache_offsets.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     L.kvp_aux_cache_offsets.restype = C.c_int
     L.kvp_profile_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -142,6 +153,33 @@ def _shape(m) -> ModelShape:
     return sh
 
 
+def _config(cfg, max_batch: int, max_seq: int) -> Config:
+    """kvp_config for an object with the fields of kvp_synth.KVPConfig (the arrays it points to stay
+    alive as attributes of the returned structure)."""
+    c = Config()
+    sb, sa = _shape(cfg.base), _shape(cfg.aux)
+    c.base, c.aux = sb, sa
+    c.vocab = cfg.vocab
+    c.dtype = DTYPE_F32 if cfg.dtype == "fp32" else DTYPE_BF16
+    c.rope_theta, c.rms_eps = cfg.rope_theta, cfg.rms_eps
+    lm = (C.c_int32 * len(cfg.layer_map))(*cfg.layer_map)
+    c.layer_map = C.cast(lm, C.POINTER(C.c_int32))
+    c.max_batch, c.max_seq = max_batch, max_seq
+    c._keep = (sb, sa, lm)
+    return c
+
+
+def kvp_debug_plan(cfg, B: int, T: int, max_batch: Optional[int] = None, max_seq: Optional[int] = None):
+    """The workspace plan of a B x T call, computed on the host (no GPU needed): returns
+    (regions, total_bytes) with regions = [(name, offset, bytes, bytes_touched), ...] in address order."""
+    c = _config(cfg, max_batch or B, max_seq or T)
+    n, total = C.c_int32(), C.c_uint64()
+    _check(lib().kvp_debug_plan(C.byref(c), B, T, None, 0, C.byref(n), C.byref(total)))
+    arr = (PlanRegion * n.value)()
+    _check(lib().kvp_debug_plan(C.byref(c), B, T, arr, n.value, C.byref(n), C.byref(total)))
+    return [(r.name.decode(), int(r.offset), int(r.bytes), int(r.bytes_touched)) for r in arr], int(total.value)
+
+
 def kvp_load_weights(cfg, tensors: Mapping[str, "object"], max_batch: int, max_seq: int) -> int:
     """cfg: an object with the fields of kvp_synth.KVPConfig; tensors: name -> contiguous device
     tensor in the configuration's dtype (names as in kvp_synth.tensor_specs; the auxiliary
@@ -163,15 +201,7 @@ def kvp_load_weights(cfg, tensors: Mapping[str, "object"], max_batch: int, max_s
         mw._keep = keep
         return mw
 
-    c = Config()
-    sb, sa = _shape(cfg.base), _shape(cfg.aux)
-    c.base, c.aux = sb, sa
-    c.vocab = cfg.vocab
-    c.dtype = DTYPE_F32 if cfg.dtype == "fp32" else DTYPE_BF16
-    c.rope_theta, c.rms_eps = cfg.rope_theta, cfg.rms_eps
-    lm = (C.c_int32 * len(cfg.layer_map))(*cfg.layer_map)
-    c.layer_map = C.cast(lm, C.POINTER(C.c_int32))
-    c.max_batch, c.max_seq = max_batch, max_seq
+    c = _config(cfg, max_batch, max_seq)
     w = Weights()
     w.base, w.aux = model("base", cfg.base), model("aux", cfg.aux)
     pk = _ptr_array([tensors.get(f"pred.L{i}.wk") for i in range(cfg.base.n_layers)])
@@ -220,6 +250,12 @@ def kvp_generation_step(handle: int, tokens, B: int, pos: int, k_cache, v_cache,
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().kvp_generation_step(handle, _ptr(tokens), B, pos, _ptr(k_cache), _ptr(v_cache), T_cap,
                                      _ptr(logits), _ptr(argmax), _ptr(workspace), ws_bytes, stream))
+
+
+def kvp_check_flags(handle: int, clear: bool = False) -> int:
+    v = C.c_uint32()
+    _check(lib().kvp_check_flags(handle, C.byref(v), 1 if clear else 0))
+    return int(v.value)
 
 
 def kvp_free(handle: int) -> None:
@@ -308,6 +344,10 @@ class KVP:
         s = self.torch.cuda.current_stream().cuda_stream if stream is None else stream
         kvp_generation_step(self.handle, tokens, B, pos, self.k_cache, self.v_cache, self.T_cap, self.logits,
                             self.argmax, self.workspace, s)
+
+    def check_flags(self, clear: bool = False) -> int:
+        """KVP_FLAG_* bits set by the kernels of earlier calls (synchronise first)."""
+        return kvp_check_flags(self.handle, clear)
 
     def aux_cache_layer(self, l: int, B: int, T: int):
         """Dense views [B*T, n_kv_l*hd] of auxiliary layer l's keys and values in the workspace

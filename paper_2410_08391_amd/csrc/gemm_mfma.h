@@ -3,11 +3,13 @@
 // supplied by small functors, so one kernel serves the QKV (+rotary), O/down (+residual),
 // gate/up (+SiLU*mul) and predictor (+cache scatter) projections.
 //
-// Tiling.  A block computes a BM x BN tile with WM x WN wavefronts; K advances in steps of
-// 64.  Operand tiles are staged in LDS, double buffered, as rows of 64 bf16 (128 B) whose
-// eight 16-byte chunks are XOR-swizzled with the row index so that the MFMA fragment reads are
-// bank-conflict free.  Global loads for step i+1 are issued
-// before the MFMAs of step i and land in LDS after them (register staging).
+// Tiling.  A block computes a BM x BN tile with WM x WN wavefronts; K advances in tiles of 64.
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no register
+// staging) as rows of 64 bf16 (128 B) whose eight 16-byte chunks are XOR-swizzled with the row
+// index so that the MFMA fragment reads are bank-conflict free.  NS stages form a ring: the
+// prologue requests NS tiles, every K tile requests tile kt + NS into the stage it has just
+// freed, and waits (explicit vmcnt) only for tile kt + 1.  Fragments are double buffered in
+// registers, so the LDS reads of a sub-step ride behind the MFMAs of the one before.
 //
 // Column pairing.  The BN virtual columns of a block are two halves of BN/2; a wavefront
 // owns the same column positions in both halves, so the epilogue sees, in one lane, output p
@@ -204,7 +206,6 @@ __global__ __launch_bounds__(Tile::THREADS) void gemm_bf16_kernel(const bf16* __
 #pragma unroll
       for (int j = 0; j < MF; ++j) {
         acc[j / CT][j % CT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j % CT], af[set][j / CT], acc[j / CT][j % CT], 0, 0, 0);
-#ifndef KVP_DBG_NO_LDSREAD
         {
           constexpr int RPER = (RD + MF - 1) / MF;    // fragment reads riding behind each MFMA
 #pragma unroll
@@ -216,8 +217,6 @@ __global__ __launch_bounds__(Tile::THREADS) void gemm_bf16_kernel(const bf16* __
             }
           }
         }
-#endif
-#ifndef KVP_DBG_NO_GLOBAL
         if (has_load && ks == KS - 1) {
           constexpr int PER = (GA + GB + MF - 1) / MF;
 #pragma unroll
@@ -226,7 +225,6 @@ __global__ __launch_bounds__(Tile::THREADS) void gemm_bf16_kernel(const bf16* __
             if (idx < GA + GB) issue_one(cur, koff, idx);
           }
         }
-#endif
         __builtin_amdgcn_sched_barrier(0);
       }
     }

@@ -203,7 +203,7 @@ template bool launch_absorb_o<bf16>(const float*, const bf16*, float*, bf16*, bf
 //   ka   [B*T][KA] token-major keys of the auxiliary layer
 //   vT   [B][KA][T_pad] its values transposed (column c of token t at [c][t]; T_pad a multiple
 //        of 64, entries t >= T finite)
-//   part [n_splits][B][n_q][KA + 2]: unnormalised sums, running maximum (natural log), sum of
+//   part [n_splits][B][n_q][KA + kPartPad]: unnormalised sums, running maximum (natural log), sum of
 //        weights: the format decode_attn_combine_kernel merges.
 // Grid (n_splits, ceil(n_q / 16), B), 4 waves; wave w takes the 32-key pieces w, w + 4, .. of the
 // block's chunk.  Per piece:
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void absorbed_attn_mfma_kernel(const float* __
   for (int i = tid; i < 16 * VC; i += 256) {
     const int hh = i / VC, c = i % VC;
     if (h0 + hh >= n_q) continue;
-    float* pr = part + (((size_t)split * B + b) * n_q + h0 + hh) * (KA + 2);
+    float* pr = part + (((size_t)split * B + b) * n_q + h0 + hh) * (KA + kPartPad);
     pr[vc0 + c] = o_sh[hh * OST + c];
     if (c == 0 && vc0 == 0) {                      // (every column block computes the same statistics)
       const float mb = fmaxf(fmaxf(st_m[0][hh], st_m[1][hh]), fmaxf(st_m[2][hh], st_m[3][hh]));

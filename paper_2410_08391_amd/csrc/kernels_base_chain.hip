@@ -34,14 +34,16 @@ __device__ __forceinline__ void split_store(bf16* hi, bf16* lo, size_t idx, floa
 }
 
 // y[b,:] = E[last token of sequence b]; hi/lo = split(y * gain); ssq[b] = sum(y^2).  One block per b.
+// A token id outside [0, vocab) is clamped and sets bit 0 of *flags.
 __global__ __launch_bounds__(256) void base_embed_kernel(const int32_t* __restrict__ tokens, int T_len,
                                                          const bf16* __restrict__ E, int vocab,
                                                          const bf16* __restrict__ gain, float* __restrict__ y,
                                                          bf16* __restrict__ uh, bf16* __restrict__ ul,
-                                                         float* __restrict__ ssq, int d) {
+                                                         float* __restrict__ ssq, int d, uint32_t* __restrict__ flags) {
   __shared__ float red[4];
   const int b = blockIdx.x;
   int tok = tokens[(size_t)b * T_len + T_len - 1];
+  if ((tok < 0 || tok >= vocab) && threadIdx.x == 0) atomicOr(flags, 1u);
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const bf16* e = E + (size_t)tok * d;
   float ss = 0.f;
@@ -85,7 +87,7 @@ struct ChainArgs {
   float* ssq_out;         // MODE 1: [B, gridDim.x] partial sums of y_new^2
   int B, N, K;
   // gemv_rows_kernel<.., MERGE>: the right-hand side is the merge of decode-attention split partials
-  // [n_splits][B][n_q][hd + 2] (hd un-normalised sums, running maximum, normaliser), K = n_q * hd
+  // [n_splits][B][n_q][hd + kPartPad] (hd un-normalised sums, running maximum, normaliser), K = n_q * hd
   const float* part = nullptr;
   int n_splits = 0, n_q = 0, hd = 0;
 };
@@ -426,7 +428,7 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(ChainArgs a) {
   // Same operations, in the same order per element, as decode_attn_combine_kernel (splits in
   // batches of eight).
   auto stage_merged = [&](int k0) {
-    const size_t stride = (size_t)a.B * a.n_q * (a.hd + 2);
+    const size_t stride = (size_t)a.B * a.n_q * (a.hd + kPartPad);
 #pragma unroll 1
     for (int u = 0; u < XU; ++u) {
       const int kl = ((int)threadIdx.x + u * 256) * 8;
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(ChainArgs a) {
         float l = 1.f;
         if (k8 < K) {
           const int hq = k8 / a.hd, d = k8 % a.hd;
-          const float* p0 = a.part + ((size_t)b * a.n_q + hq) * (a.hd + 2);
+          const float* p0 = a.part + ((size_t)b * a.n_q + hq) * (a.hd + kPartPad);
           float m = -INFINITY;
           l = 0.f;
           for (int s0 = 0; s0 < a.n_splits; s0 += 8) {
@@ -669,8 +671,8 @@ static void launch_chain(ChainArgs a, hipStream_t s) {
 }
 
 void launch_base_embed(const int32_t* tokens, int T_len, const bf16* E, int vocab, const bf16* gain, float* y, bf16* uh,
-                       bf16* ul, float* ssq, int B, int d, hipStream_t s) {
-  hipLaunchKernelGGL(base_embed_kernel, dim3(B), dim3(256), 0, s, tokens, T_len, E, vocab, gain, y, uh, ul, ssq, d);
+                       bf16* ul, float* ssq, int B, int d, uint32_t* flags, hipStream_t s) {
+  hipLaunchKernelGGL(base_embed_kernel, dim3(B), dim3(256), 0, s, tokens, T_len, E, vocab, gain, y, uh, ul, ssq, d, flags);
 }
 void launch_chain_project(const bf16* W, const bf16* xh, const bf16* xl, const float* ssq_in, int n_part_in, float eps,
                           float* out, int B, int N, int K, hipStream_t s) {

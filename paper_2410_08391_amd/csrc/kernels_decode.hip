@@ -175,7 +175,7 @@ template void launch_gemv<float>(int, bool, const float*, const float*, const fl
 //   q      float [B, n_q*hd]  raw query projection; rotary (position T-1) and 1/sqrt(hd) are
 //          applied here while staging q in LDS.
 //   cache  T [B][n_kv][T_cap][hd] for this layer (keys post-rotary as predicted).
-//   part   float [n_splits][B][n_q][hd + 2]: un-normalised sum, running max, running denominator.
+//   part   float [n_splits][B][n_q][hd + kPartPad]: un-normalised sum, running max, running denominator.
 // A row of hd elements is covered by LPR = hd/8 lanes (16-byte loads); a wave reads 64/LPR rows
 // per load instruction, U such instructions per tensor form one batch, and the next batch's
 // loads are issued before the current batch is consumed.  Every lane group keeps its own
@@ -224,11 +224,7 @@ __global__ __launch_bounds__(256) void decode_attn_split_kernel(const float* __r
   constexpr int LPR = HD / 8;           // lanes per cache row
   constexpr int RPW = kWave / LPR;      // rows per wave per load
   constexpr int NGRP = 4 * RPW;         // lane groups per block
-#ifdef KVP_DEC_U
-  constexpr int U = KVP_DEC_U;
-#else
-  constexpr int U = 4;
-#endif
+  constexpr int U = 4;                  // load instructions per tensor and batch
   typedef typename Raw8<T>::type raw8;
   __shared__ float q_sh[G][HD];
   __shared__ float st_m[4][G], st_l[4][G];
@@ -372,7 +368,7 @@ __global__ __launch_bounds__(256) void decode_attn_split_kernel(const float* __r
       l += st_l[p][g] * w;
       o += st_o[p][g][d] * w;
     }
-    float* pr = part + (((size_t)split * B + b) * n_q + (size_t)hk * G + g) * (HD + 2);
+    float* pr = part + (((size_t)split * B + b) * n_q + (size_t)hk * G + g) * (HD + kPartPad);
     pr[d] = o;
     if (d == 0) { pr[HD] = m; pr[HD + 1] = l; }
   }
@@ -386,8 +382,8 @@ __global__ void decode_attn_combine_kernel(const float* __restrict__ part, float
                                            bf16* __restrict__ out_hi, bf16* __restrict__ out_lo, int n_splits, int B,
                                            int n_q, int hd) {
   const int hq = blockIdx.x, b = blockIdx.y;
-  const size_t stride = (size_t)B * n_q * (hd + 2);
-  const float* p0 = part + ((size_t)b * n_q + hq) * (hd + 2);
+  const size_t stride = (size_t)B * n_q * (hd + kPartPad);
+  const float* p0 = part + ((size_t)b * n_q + hq) * (hd + kPartPad);
   for (int d = threadIdx.x; d < hd; d += blockDim.x) {
     float m = -INFINITY, l = 0.f, o = 0.f;
     for (int s0 = 0; s0 < n_splits; s0 += 8) {
@@ -622,7 +618,7 @@ __global__ __launch_bounds__(256) void decode_attn_mfma_kernel(const float* __re
       l += st_l[p][hh] * w;
       o += st_o[p][hh][d] * w;
     }
-    float* pr = part + (((size_t)split * B + b) * n_q + (size_t)hk * G + hh) * (HD + 2);
+    float* pr = part + (((size_t)split * B + b) * n_q + (size_t)hk * G + hh) * (HD + kPartPad);
     pr[d] = o;
     if (d == 0) { pr[HD] = m * 0.6931471805599453f; pr[HD + 1] = l; }   // the merge kernel works with e^x
   }

@@ -26,18 +26,21 @@ void launch_rope_table(float2* tab, int max_pos, int half, double theta, hipStre
 
 // ---------------------------------------------------------------------------------------
 // Embedding gather fused with the first RMSNorm:  x[n,:] = E[tok[n],:],  h = rmsnorm(x) * g.
-// One wavefront per token.  Token ids are clamped into [0, vocab).
+// One wavefront per token.  Token ids are clamped into [0, vocab); a clamped id sets bit 0 of
+// *flags (KVP_FLAG_TOKEN_CLAMPED), which kvp_check_flags reports.
 // `tok_stride`/`tok_offset` pick token n as tokens[n * tok_stride + tok_offset] (the base step
 // gathers the last token of each sequence: stride T, offset T-1).
 // ---------------------------------------------------------------------------------------
 template <typename T, typename HT>
 __global__ void embed_rmsnorm_kernel(const int32_t* __restrict__ tokens, int tok_stride, int tok_offset,
                                      const T* __restrict__ E, int vocab, const T* __restrict__ gain,
-                                     float* __restrict__ x, HT* __restrict__ h, int n_tokens, int d, float eps) {
+                                     float* __restrict__ x, HT* __restrict__ h, int n_tokens, int d, float eps,
+                                     uint32_t* __restrict__ flags) {
   int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
   int lane = threadIdx.x % kWave;
   if (wave >= n_tokens) return;
   int tok = tokens[(size_t)wave * tok_stride + tok_offset];
+  if ((tok < 0 || tok >= vocab) && lane == 0) atomicOr(flags, 1u);
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const T* e = E + (size_t)tok * d;
   float* xr = x + (size_t)wave * d;
@@ -310,10 +313,10 @@ template void launch_rows_to_cache<bf16>(const bf16*, bf16*, int, int, int64_t, 
 // ---------------------------------------------------------------------------------------
 template <typename T, typename HT>
 void launch_embed_rmsnorm(const int32_t* tokens, int tok_stride, int tok_offset, const T* E, int vocab,
-                          const T* gain, float* x, HT* h, int n_tokens, int d, float eps, hipStream_t s) {
+                          const T* gain, float* x, HT* h, int n_tokens, int d, float eps, uint32_t* flags, hipStream_t s) {
   int blocks = (n_tokens + 3) / 4;
   hipLaunchKernelGGL((embed_rmsnorm_kernel<T, HT>), dim3(blocks), dim3(256), 0, s, tokens, tok_stride, tok_offset,
-                     E, vocab, gain, x, h, n_tokens, d, eps);
+                     E, vocab, gain, x, h, n_tokens, d, eps, flags);
 }
 __device__ __forceinline__ void load4(const float* p, float (&o)[4]) {
   f32x4 v = *reinterpret_cast<const f32x4*>(p);
@@ -418,7 +421,7 @@ void launch_attn_prefill_generic(const T* q, const T* k, const T* v, T* out, int
 
 #define KVP_INST(T)                                                                                                   \
   template void launch_embed_rmsnorm<T, T>(const int32_t*, int, int, const T*, int, const T*, float*, T*, int, int,  \
-                                           float, hipStream_t);                                                      \
+                                           float, uint32_t*, hipStream_t);                                           \
   template void launch_rmsnorm<T, T>(const float*, const T*, T*, int, int, float, hipStream_t);                      \
   template void launch_rope<T>(T*, int, int, int, int, int, const float2*, hipStream_t);                             \
   template void launch_silu_mul<T>(const T*, T*, size_t, int, hipStream_t);                                          \
@@ -430,7 +433,7 @@ void launch_attn_prefill_generic(const T* q, const T* k, const T* v, T* out, int
 KVP_INST(float)
 KVP_INST(bf16)
 template void launch_embed_rmsnorm<bf16, float>(const int32_t*, int, int, const bf16*, int, const bf16*, float*, float*,
-                                                int, int, float, hipStream_t);
+                                                int, int, float, uint32_t*, hipStream_t);
 template void launch_rmsnorm<bf16, float>(const float*, const bf16*, float*, int, int, float, hipStream_t);
 
 }  // namespace kvp

@@ -56,6 +56,11 @@ struct Workspace {   // byte offsets into the caller's workspace
   int plan_T;     // attention length the splits were planned for
 };
 
+struct PlanRegion {   // one carved region of the workspace, for kvp_debug_plan
+  const char* name;
+  size_t offset, bytes;
+};
+
 }  // namespace
 
 struct kvp_handle {
@@ -80,6 +85,9 @@ struct kvp_handle {
   float2* rope_aux = nullptr;  // device [max_seq][aux.hd/2]
   float2* rope_base = nullptr; // device [max_seq][base.hd/2]
   void* mfma_tables = nullptr; // device tables of the MFMA predictor
+  uint32_t* flags = nullptr;   // device word of KVP_FLAG_* bits set by kernels (kvp_check_flags)
+  int pred_main = -1;          // KVP_PRED_MAIN at load time: 0 / 1 force the predictor's stream, -1 = by prompt size
+  int device = -1;             // HIP device the handle was loaded on
   // second stream for running the base chain beside the auxiliary chain (see run_overlapped)
   hipStream_t side = nullptr;
   hipEvent_t ev_start = nullptr, ev_done = nullptr;
@@ -112,48 +120,58 @@ int absorbed_splits_bound(const kvp_handle* h, int B, int n_q, int Ka, int T) {
   return want < by_len ? want : by_len;
 }
 
-Workspace plan_workspace(const kvp_handle* h, int B, int T) {
+// Carves the caller's workspace for a B x T call.  base_only: only what one base-model step over
+// an existing cache needs (the generation loop) -- no auxiliary cache, no prefill activations, no
+// buffers of the absorbed step; T is then the attention length.  `regions` (optional) receives
+// every carved region in order.
+Workspace plan_workspace(const kvp_handle* h, int B, int T, bool base_only = false, std::vector<PlanRegion>* regions = nullptr) {
   const kvp_config& c = h->cfg;
-  size_t N = (size_t)B * T, es = h->esize;
+  size_t N = base_only ? 0 : (size_t)B * T, es = h->esize;
   size_t Ka = (size_t)c.aux.n_kv_heads * c.aux.head_dim, qa = (size_t)c.aux.n_q_heads * c.aux.head_dim;
   size_t qb = (size_t)c.base.n_q_heads * c.base.head_dim;
   Workspace w{};
   size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-  w.aux_k = take((size_t)c.aux.n_layers * N * Ka * es);
-  w.aux_v = take((size_t)c.aux.n_layers * N * Ka * es);
-  w.x = take(N * c.aux.d_model * sizeof(float));
-  w.h = take(N * c.aux.d_model * es);
-  w.q = take(N * qa * es);
-  w.attn = take(N * qa * es);
-  w.gu = take(h->use_mfma ? 0 : N * 2 * (size_t)c.aux.ffn_dim * es);
-  w.act = take(N * (size_t)c.aux.ffn_dim * es);
-  w.vt_layer = h->use_mfma ? align_up(mfma_vt_bytes(&c, B, T)) : 0;
-  w.vt = take(w.vt_layer * c.aux.n_layers);
-  w.y = take((size_t)B * c.base.d_model * sizeof(float));
-  w.bq = take((size_t)B * qb * sizeof(float));
-  w.bk = take((size_t)B * c.base.n_kv_heads * c.base.head_dim * sizeof(float));   // generation step: own key / value
-  w.bv = take((size_t)B * c.base.n_kv_heads * c.base.head_dim * sizeof(float));
-  w.battn = take((size_t)B * qb * sizeof(float));
-  w.bact = take((size_t)B * c.base.ffn_dim * sizeof(float));
+  auto take = [&](const char* name, size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes);
+    if (regions) regions->push_back(PlanRegion{name, o, bytes});
+    return o;
+  };
+  w.aux_k = take("aux_k", (size_t)c.aux.n_layers * N * Ka * es);
+  w.aux_v = take("aux_v", (size_t)c.aux.n_layers * N * Ka * es);
+  w.x = take("x", N * c.aux.d_model * sizeof(float));
+  w.h = take("h", N * c.aux.d_model * es);
+  w.q = take("q", N * qa * es);
+  w.attn = take("attn", N * qa * es);
+  w.gu = take("gu", h->use_mfma ? 0 : N * 2 * (size_t)c.aux.ffn_dim * es);
+  w.act = take("act", N * (size_t)c.aux.ffn_dim * es);
+  w.vt_layer = (h->use_mfma && !base_only) ? align_up(mfma_vt_bytes(&c, B, T)) : 0;
+  w.vt = take("vt", w.vt_layer * c.aux.n_layers);
+  w.y = take("y", (size_t)B * c.base.d_model * sizeof(float));
+  w.bq = take("bq", (size_t)B * qb * sizeof(float));
+  w.bk = take("bk", (size_t)B * c.base.n_kv_heads * c.base.head_dim * sizeof(float));   // generation step: own key / value
+  w.bv = take("bv", (size_t)B * c.base.n_kv_heads * c.base.head_dim * sizeof(float));
+  w.battn = take("battn", (size_t)B * qb * sizeof(float));
+  w.bact = take("bact", (size_t)B * c.base.ffn_dim * sizeof(float));
   w.n_splits = decode_attn_splits(B, c.base.n_kv_heads, T);
   w.plan_T = T;
   size_t part_elems = 0;                       // layers of different width split differently: size for the largest
   for (int i = 0; i < c.base.n_layers; ++i) {
-    size_t e = (size_t)decode_attn_splits(B, h->b_nkv[i], T) * B * h->b_nq[i] * (c.base.head_dim + 2);
+    size_t e = (size_t)decode_attn_splits(B, h->b_nkv[i], T) * B * h->b_nq[i] * (c.base.head_dim + kPartPad);
     if (e > part_elems) part_elems = e;
+    if (base_only) continue;
     const int Ka_i = h->a_nkv[h->layer_map[i]] * c.aux.head_dim;       // the absorbed step's partials are Ka wide
-    e = (size_t)absorbed_splits_bound(h, B, h->b_nq[i], Ka_i, T) * B * h->b_nq[i] * (Ka_i + 2);
+    e = (size_t)absorbed_splits_bound(h, B, h->b_nq[i], Ka_i, T) * B * h->b_nq[i] * (Ka_i + kPartPad);
     if (e > part_elems) part_elems = e;
   }
-  w.part = take(part_elems * sizeof(float));
-  w.qw = take((size_t)B * c.base.n_q_heads * Ka * sizeof(float));
-  w.rw = take((size_t)B * c.base.n_q_heads * Ka * sizeof(float));
-  w.logits = take((size_t)B * c.vocab * sizeof(float));
-  w.uh = take((size_t)B * c.base.d_model * 2); w.ul = take((size_t)B * c.base.d_model * 2);
-  w.oh = take((size_t)B * qb * 2); w.ol = take((size_t)B * qb * 2);
-  w.ah = take((size_t)B * c.base.ffn_dim * 2); w.al = take((size_t)B * c.base.ffn_dim * 2);
-  w.ssq = take((size_t)B * chain_ssq_parts(c.base.d_model, B) * sizeof(float));
+  w.part = take("part", part_elems * sizeof(float));
+  w.qw = take("qw", base_only ? 0 : (size_t)B * c.base.n_q_heads * Ka * sizeof(float));
+  w.rw = take("rw", base_only ? 0 : (size_t)B * c.base.n_q_heads * Ka * sizeof(float));
+  w.logits = take("logits", (size_t)B * c.vocab * sizeof(float));
+  w.uh = take("uh", (size_t)B * c.base.d_model * 2); w.ul = take("ul", (size_t)B * c.base.d_model * 2);
+  w.oh = take("oh", (size_t)B * qb * 2); w.ol = take("ol", (size_t)B * qb * 2);
+  w.ah = take("ah", (size_t)B * c.base.ffn_dim * 2); w.al = take("al", (size_t)B * c.base.ffn_dim * 2);
+  w.ssq = take("ssq", (size_t)B * chain_ssq_parts(c.base.d_model, B) * sizeof(float));
   w.total = off;
   return w;
 }
@@ -224,7 +242,7 @@ int run_stack(kvp_handle* h, const Stack& st, const PrefillBufs& pb, char* ws, c
     if (l == 0) {
       Timed t(h, s, KVP_KC_EMBED_NORM);
       launch_embed_rmsnorm<T, T>(tokens, 1, 0, (const T*)mw.embed, c.vocab, (const T*)mw.attn_norm[0], x, hbuf,
-                                 N, d, c.rms_eps, s);
+                                 N, d, c.rms_eps, h->flags, s);
     } else {
       Timed t(h, s, KVP_KC_EMBED_NORM);
       launch_rmsnorm<T, T>(x, (const T*)mw.attn_norm[l], hbuf, N, d, c.rms_eps, s);
@@ -397,7 +415,8 @@ struct BaseChain {
     const kvp_config& c = h->cfg;
     Timed t(h, s, KVP_KC_EMBED_NORM);
     launch_base_embed(tokens, append >= 0 ? 1 : T_len, (const bf16*)h->base.embed, c.vocab,
-                      (const bf16*)h->base.attn_norm[0], f32(w.y), b16(w.uh), b16(w.ul), f32(w.ssq), B, c.base.d_model, s);
+                      (const bf16*)h->base.attn_norm[0], f32(w.y), b16(w.uh), b16(w.ul), f32(w.ssq), B, c.base.d_model,
+                      h->flags, s);
   }
   int layer(int i) {
     const kvp_config& c = h->cfg;
@@ -507,8 +526,7 @@ int run_overlapped(kvp_handle* h, const Workspace& w, char* ws, const int32_t* t
   // auxiliary layers (measured: TTFT -2.5 % at 1 x 1024 tokens, -1.7 % at 4 x 2048, -2 % at 8 x 2048); at 32768 tokens
   // it stays on the internal stream, where its cache writes run beside the auxiliary GEMMs (there the other order is
   // 0.2 % slower).
-  const char* pm = getenv("KVP_PRED_MAIN");            // "0" / "1": tuning override
-  const bool pred_main = pm ? pm[0] == '1' : (size_t)B * T_len <= 16384;
+  const bool pred_main = h->pred_main >= 0 ? h->pred_main == 1 : (size_t)B * T_len <= 16384;   // (KVP_PRED_MAIN=0|1 at load time overrides)
   auto predict_layer = [&](int l, hipStream_t st) {   // predictor for every run of base layers fed by auxiliary layer l
     for (int i = 0; i < LB && !absorbed;) {
       if (h->layer_map[i] != l) { ++i; continue; }
@@ -529,24 +547,23 @@ int run_overlapped(kvp_handle* h, const Workspace& w, char* ws, const int32_t* t
     }
     if (!pred_main) predict_layer(l, sb);
     if (rc_hook != KVP_OK) return;
-    while (next_base < LB && h->layer_map[next_base] <= l) {   // base layers are sequential
-      bool fed = true;                                         // all earlier groups are issued: layer is ready
-      if (fed) { int rc = bc.layer(next_base); if (rc != KVP_OK) { rc_hook = rc; return; } }
+    // base layers run in order: layer i may go once every auxiliary layer up to j_i is enqueued
+    while (next_base < LB && h->layer_map[next_base] <= l) {
+      int rc = bc.layer(next_base);
+      if (rc != KVP_OK) { rc_hook = rc; return; }
       ++next_base;
     }
   };
   int rc = run_aux<bf16>(h, w, ws, tokens, B, T_len, s, kv_ready);
   if (rc == KVP_OK) rc = rc_hook;
   if (rc == KVP_OK && absorbed && predict) rc = run_predict<bf16>(h, w, ws, B, T_len, k_cache, v_cache, T_cap, s);
-  if (rc != KVP_OK) return rc;
-  for (; next_base < LB; ++next_base) {
-    rc = bc.layer(next_base);
-    if (rc != KVP_OK) return rc;
-  }
-  bc.end();
+  for (; rc == KVP_OK && next_base < LB; ++next_base) rc = bc.layer(next_base);
+  if (rc == KVP_OK) bc.end();
+  // The internal stream joins the caller's stream on the error paths too: whatever was enqueued on it
+  // before the failure must not outlive the call (and a capture through the caller's stream stays valid).
   if (hipEventRecord(h->ev_done, sb) != hipSuccess || hipStreamWaitEvent(s, h->ev_done, 0) != hipSuccess)
-    return fail(KVP_ERR_HIP, "could not join the internal stream");
-  return KVP_OK;
+    return rc != KVP_OK ? rc : fail(KVP_ERR_HIP, "could not join the internal stream");
+  return rc;
 }
 
 // b <- B(I[-1], KV^_B): the base model computes a query only; keys and values come from the
@@ -568,7 +585,7 @@ int run_base(kvp_handle* h, const Workspace& w, char* ws, const int32_t* tokens,
     Timed t(h, s, KVP_KC_EMBED_NORM);
     // generation step (append >= 0): one token per sequence; else the last of T_len prompt tokens
     launch_embed_rmsnorm<T, float>(tokens, append >= 0 ? 1 : T_len, append >= 0 ? 0 : T_len - 1, (const T*)h->base.embed,
-                                   c.vocab, nullptr, y, nullptr, B, d, c.rms_eps, s);
+                                   c.vocab, nullptr, y, nullptr, B, d, c.rms_eps, h->flags, s);
   }
   const int attn_len = append >= 0 ? append + 1 : T_len;
   for (int i = 0; i < n_layers; ++i) {
@@ -812,9 +829,10 @@ extern "C" {
 const char* kvp_last_error(void) { return g_err; }
 const char* kvp_version(void) { return "libkvp 0.1 (gfx950)"; }
 
-int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle** out) {
-  if (out) *out = nullptr;
-  if (!cfg || !wts || !out) return fail(KVP_ERR_NULL, "kvp_load_weights: NULL argument");
+// Host half of kvp_load_weights: validates the configuration and fills the handle's host-side plan
+// (shapes, per-layer widths, layer map, kernel family).  Touches no device; kvp_debug_plan uses it alone.
+static int init_host(const kvp_config* cfg, kvp_handle** out) {
+  *out = nullptr;
   if (!cfg->layer_map) return fail(KVP_ERR_NULL, "layer_map is NULL");
   int rc;
   if ((rc = check_shape("base", cfg->base)) != KVP_OK) return rc;
@@ -829,8 +847,6 @@ int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle**
       return fail(KVP_ERR_BAD_CONFIG, "layer_map[%d] = %d outside [0, %d)", i, cfg->layer_map[i], cfg->aux.n_layers);
   if (!cfg->base.layer_n_q_heads && !decode_attn_supported(cfg->base.head_dim, cfg->base.n_q_heads / cfg->base.n_kv_heads))
     return fail(KVP_ERR_BAD_CONFIG, "base: head_dim must be 16/32/64/128 and n_q/n_kv one of 1,2,3,4,6,8");
-  if (!wts->pred_wk || !wts->pred_wv) return fail(KVP_ERR_NULL, "pred_wk / pred_wv is NULL");
-
   kvp_handle* h = new (std::nothrow) kvp_handle();
   if (!h) return fail(KVP_ERR_HIP, "out of host memory");
   h->cfg = *cfg;
@@ -838,15 +854,34 @@ int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle**
   h->cfg.layer_map = h->layer_map.data();
   h->esize = cfg->dtype == KVP_DTYPE_F32 ? 4 : 2;
   if ((rc = copy_widths("base", cfg->base, true, h->b_nq, h->b_nkv, h->b_f)) != KVP_OK ||
-      (rc = copy_widths("aux", cfg->aux, false, h->a_nq, h->a_nkv, h->a_f)) != KVP_OK ||
-      (rc = copy_model("base", cfg->base, wts->base, h->base, true)) != KVP_OK ||
-      (rc = copy_model("aux", cfg->aux, wts->aux, h->aux, false)) != KVP_OK) {
+      (rc = copy_widths("aux", cfg->aux, false, h->a_nq, h->a_nkv, h->a_f)) != KVP_OK) {
     delete h;
     return rc;
   }
   // the caller's width arrays were copied; the handle's configuration keeps the maxima only
   h->cfg.base.layer_n_q_heads = h->cfg.base.layer_n_kv_heads = h->cfg.base.layer_ffn_dim = nullptr;
   h->cfg.aux.layer_n_q_heads = h->cfg.aux.layer_n_kv_heads = h->cfg.aux.layer_ffn_dim = nullptr;
+  const char* force = getenv("KVP_FORCE_GENERIC");
+  h->force_generic = force && force[0] == '1';
+  h->use_mfma = stack_mfma(h, h->cfg.aux);
+  const char* pm = getenv("KVP_PRED_MAIN");            // "0" / "1": which stream runs the predictor (tuning override)
+  h->pred_main = pm ? (pm[0] == '1' ? 1 : 0) : -1;
+  *out = h;
+  return KVP_OK;
+}
+
+int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !wts || !out) return fail(KVP_ERR_NULL, "kvp_load_weights: NULL argument");
+  kvp_handle* h = nullptr;
+  int rc = init_host(cfg, &h);
+  if (rc != KVP_OK) return rc;
+  if (!wts->pred_wk || !wts->pred_wv) { delete h; return fail(KVP_ERR_NULL, "pred_wk / pred_wv is NULL"); }
+  if ((rc = copy_model("base", cfg->base, wts->base, h->base, true)) != KVP_OK ||
+      (rc = copy_model("aux", cfg->aux, wts->aux, h->aux, false)) != KVP_OK) {
+    delete h;
+    return rc;
+  }
   for (int i = 0; i < cfg->base.n_layers; ++i) {
     if (!wts->pred_wk[i] || !wts->pred_wv[i]) { delete h; return fail(KVP_ERR_NULL, "pred_wk/pred_wv[%d] is NULL", i); }
     if (!aligned16(wts->pred_wk[i]) || !aligned16(wts->pred_wv[i])) {
@@ -856,15 +891,17 @@ int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle**
     h->pred_wk.push_back(wts->pred_wk[i]);
     h->pred_wv.push_back(wts->pred_wv[i]);
   }
-  const char* force = getenv("KVP_FORCE_GENERIC");
-  h->force_generic = force && force[0] == '1';
-  h->use_mfma = stack_mfma(h, h->cfg.aux);
 
-  // rotary tables, built once in double precision (a few MB; the only device memory the handle owns)
+  // Device memory the handle owns: two rotary tables built once in double precision (max_seq x head_dim / 2
+  // float2 each, a few MB), one flag word, and the predictor's pointer / layer-map tables (mfma_prepare).
+  hipError_t e = hipGetDevice(&h->device);
+  if (e != hipSuccess) { kvp_free(h); return fail(KVP_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e)); }
   size_t na = (size_t)cfg->max_seq * (cfg->aux.head_dim / 2), nb = (size_t)cfg->max_seq * (cfg->base.head_dim / 2);
-  hipError_t e = hipMalloc((void**)&h->rope_aux, na * sizeof(float2));
+  e = hipMalloc((void**)&h->rope_aux, na * sizeof(float2));
   if (e == hipSuccess) e = hipMalloc((void**)&h->rope_base, nb * sizeof(float2));
-  if (e != hipSuccess) { kvp_free(h); return fail(KVP_ERR_HIP, "hipMalloc(rotary table): %s", hipGetErrorString(e)); }
+  if (e == hipSuccess) e = hipMalloc((void**)&h->flags, 256);
+  if (e == hipSuccess) e = hipMemset(h->flags, 0, 256);
+  if (e != hipSuccess) { kvp_free(h); return fail(KVP_ERR_HIP, "hipMalloc(rotary tables, flag word): %s", hipGetErrorString(e)); }
   launch_rope_table(h->rope_aux, cfg->max_seq, cfg->aux.head_dim / 2, (double)cfg->rope_theta, nullptr);
   launch_rope_table(h->rope_base, cfg->max_seq, cfg->base.head_dim / 2, (double)cfg->rope_theta, nullptr);
   e = hipDeviceSynchronize();
@@ -886,6 +923,52 @@ int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle**
     return fail(rc, "could not build the predictor's device tables");
   }
   *out = h;
+  return KVP_OK;
+}
+
+int kvp_check_flags(kvp_handle* h, uint32_t* flags_out, int32_t clear) {
+  if (!h || !flags_out) return fail(KVP_ERR_NULL, "kvp_check_flags: NULL argument");
+  uint32_t v = 0;
+  hipError_t e = hipMemcpy(&v, h->flags, sizeof(v), hipMemcpyDeviceToHost);
+  if (e == hipSuccess && clear && v) e = hipMemset(h->flags, 0, sizeof(v));
+  if (e != hipSuccess) return fail(KVP_ERR_HIP, "kvp_check_flags: %s", hipGetErrorString(e));
+  *flags_out = v;
+  return KVP_OK;
+}
+
+int kvp_debug_plan(const kvp_config* cfg, int32_t B, int32_t T, kvp_plan_region* regions, int32_t capacity,
+                   int32_t* n_regions, uint64_t* total_bytes) {
+  if (!cfg || !n_regions || !total_bytes) return fail(KVP_ERR_NULL, "kvp_debug_plan: NULL argument");
+  kvp_handle* h = nullptr;
+  int rc = init_host(cfg, &h);
+  if (rc != KVP_OK) return rc;
+  if (B < 1 || T < 1 || B > h->cfg.max_batch || T > h->cfg.max_seq) {
+    delete h;
+    return fail(KVP_ERR_BAD_SHAPE, "B = %d, T = %d outside [1, max_batch] x [1, max_seq]", B, T);
+  }
+  std::vector<PlanRegion> rs;
+  Workspace w = plan_workspace(h, B, T, false, &rs);
+  // What the launches of a B x T call touch in the split-partial region, from the launch-side split counts
+  // (the planner sizes the region from bounds of its own; the two must agree for every shape).
+  size_t part_touched = 0;
+  for (int i = 0; i < h->cfg.base.n_layers; ++i) {
+    size_t e = (size_t)decode_attn_splits(B, h->b_nkv[i], T) * B * h->b_nq[i] * (h->cfg.base.head_dim + kPartPad);
+    if (e > part_touched) part_touched = e;
+    const int Ka_i = h->a_nkv[h->layer_map[i]] * h->cfg.aux.head_dim;
+    if (absorbed_attn_supported(Ka_i)) {
+      e = (size_t)absorbed_splits(h, B, h->b_nq[i], Ka_i, T) * B * h->b_nq[i] * (Ka_i + kPartPad);
+      if (e > part_touched) part_touched = e;
+    }
+  }
+  *n_regions = (int32_t)rs.size();
+  *total_bytes = w.total;
+  for (int i = 0; regions && i < (int)rs.size() && i < capacity; ++i) {
+    snprintf(regions[i].name, sizeof(regions[i].name), "%s", rs[i].name);
+    regions[i].offset = rs[i].offset;
+    regions[i].bytes = rs[i].bytes;
+    regions[i].bytes_touched = strcmp(rs[i].name, "part") == 0 ? part_touched * sizeof(float) : rs[i].bytes;
+  }
+  delete h;
   return KVP_OK;
 }
 
@@ -977,30 +1060,31 @@ int kvp_reference_prefill(kvp_handle* h, int32_t model, const int32_t* tokens, i
 }
 
 size_t kvp_generation_workspace_bytes(const kvp_handle* h, int32_t B, int32_t T_total) {
-  return kvp_workspace_bytes(h, B, T_total);
+  if (!h || B < 1 || T_total < 1 || B > h->cfg.max_batch || T_total > h->cfg.max_seq) return 0;
+  return plan_workspace(h, B, T_total, true).total;
 }
 
-int kvp_generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos, void* k_cache, void* v_cache,
-                        int64_t T_cap, float* logits, int32_t* argmax, void* workspace, size_t workspace_bytes,
-                        void* hip_stream) {
-  if (!h) return fail(KVP_ERR_NULL, "handle is NULL");
-  if (!tokens || !workspace || !k_cache || !v_cache) return fail(KVP_ERR_NULL, "tokens / caches / workspace is NULL");
+// Body of kvp_generation_step: `scratch_bytes` of device scratch at `scratch_mem`.
+static int generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos, void* k_cache, void* v_cache,
+                           int64_t T_cap, float* logits, int32_t* argmax, void* scratch_mem, size_t scratch_bytes,
+                           const char* scratch_name, void* hip_stream) {
+  if (!tokens || !k_cache || !v_cache) return fail(KVP_ERR_NULL, "tokens / caches is NULL");
   if (!logits && !argmax) return fail(KVP_ERR_NULL, "logits and argmax are both NULL");
   if (B < 1 || B > h->cfg.max_batch) return fail(KVP_ERR_BAD_SHAPE, "B = %d outside [1, max_batch = %d]", B, h->cfg.max_batch);
   if (pos < 1 || pos + 1 > h->cfg.max_seq) return fail(KVP_ERR_BAD_SHAPE, "pos = %d: pos + 1 must lie in [2, max_seq = %d]", pos, h->cfg.max_seq);
   if ((int64_t)pos + 1 > T_cap) return fail(KVP_ERR_BAD_SHAPE, "pos = %d does not fit T_cap = %lld", pos, (long long)T_cap);
-  if (((uintptr_t)workspace & 255) != 0) return fail(KVP_ERR_BAD_SHAPE, "workspace is not 256-byte aligned");
+  if (((uintptr_t)scratch_mem & 255) != 0) return fail(KVP_ERR_BAD_SHAPE, "%s is not 256-byte aligned", scratch_name);
   if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(logits) || ((uintptr_t)tokens & 3) || ((uintptr_t)argmax & 3))
     return fail(KVP_ERR_BAD_SHAPE, "k_cache / v_cache / logits must be 16-byte aligned, tokens / argmax 4-byte aligned");
   for (int l = 0; l < h->cfg.base.n_layers; ++l) {
     if (!h->base.wk[l] || !h->base.wv[l]) return fail(KVP_ERR_NULL, "base.wk / wv[%d] were not given to kvp_load_weights", l);
     if (h->base.qk_norm() && !h->base.k_norm[l]) return fail(KVP_ERR_NULL, "base.k_norm[%d] was not given to kvp_load_weights", l);
   }
-  Workspace w = plan_workspace(h, B, pos + 1);
-  if (workspace_bytes < w.total)
-    return fail(KVP_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  Workspace w = plan_workspace(h, B, pos + 1, true);
+  if (scratch_bytes < w.total)
+    return fail(KVP_ERR_WORKSPACE_TOO_SMALL, "%s has %zu bytes, %zu needed", scratch_name, scratch_bytes, w.total);
   hipStream_t s = (hipStream_t)hip_stream;
-  char* ws = (char*)workspace;
+  char* ws = (char*)scratch_mem;
   prof_mark(h, s, -1);
   int rc;
   if (h->cfg.dtype == KVP_DTYPE_F32)
@@ -1013,6 +1097,15 @@ int kvp_generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(KVP_ERR_HIP, "HIP error after launch: %s", hipGetErrorString(e));
   return KVP_OK;
+}
+
+int kvp_generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos, void* k_cache, void* v_cache,
+                        int64_t T_cap, float* logits, int32_t* argmax, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  if (!h) return fail(KVP_ERR_NULL, "handle is NULL");
+  if (!workspace) return fail(KVP_ERR_NULL, "workspace is NULL");
+  return generation_step(h, tokens, B, pos, k_cache, v_cache, T_cap, logits, argmax, workspace, workspace_bytes, "workspace",
+                         hip_stream);
 }
 
 int kvp_profile_enable(kvp_handle* h, int32_t on) {
@@ -1059,6 +1152,7 @@ void kvp_free(kvp_handle* h) {
   for (hipEvent_t e : h->ev_kv) if (e) (void)hipEventDestroy(e);
   if (h->rope_aux) (void)hipFree(h->rope_aux);
   if (h->rope_base) (void)hipFree(h->rope_base);
+  if (h->flags) (void)hipFree(h->flags);
   for (auto& e : h->prof_pool) (void)hipEventDestroy(e.ev);
   delete h;
 }

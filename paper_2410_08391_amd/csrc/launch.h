@@ -10,7 +10,7 @@ namespace kvp {
 void launch_rope_table(float2* tab, int max_pos, int half, double theta, hipStream_t s);
 template <typename T, typename HT>
 void launch_embed_rmsnorm(const int32_t* tokens, int tok_stride, int tok_offset, const T* E, int vocab,
-                          const T* gain, float* x, HT* h, int n_tokens, int d, float eps, hipStream_t s);
+                          const T* gain, float* x, HT* h, int n_tokens, int d, float eps, uint32_t* flags, hipStream_t s);
 template <typename T, typename HT>
 void launch_rmsnorm(const float* x, const T* gain, HT* h, int rows, int d, float eps, hipStream_t s);
 template <typename T>
@@ -39,6 +39,10 @@ template <typename T>
 void launch_rows_to_cache(const T* src, T* dst, int B, int T_len, int64_t T_cap, int n_kv, int hd, hipStream_t s);
 
 // ---- kernels_decode.hip --------------------------------------------------------------------
+// Split partials of the single-query attention kernels: one row per (split, sequence, query head) of
+// width + kPartPad floats -- `width` un-normalised sums, the running maximum, the normaliser, two unused
+// (the padding keeps every row 16-byte aligned, so a consumer reads the sums with 16-byte loads).
+constexpr int kPartPad = 4;
 // mode 0: out = W x   1: out += W x   2: out = silu(W x) * (W2 x);  norm: x = rmsnorm(x; gain)
 template <typename T>
 void launch_gemv(int mode, bool norm, const T* W, const T* W2, const float* x, const T* gain, float* out, int B, int N,
@@ -52,7 +56,7 @@ bool launch_decode_attn(const float* q, const T* kc, const T* vc, float* part, f
                         int B, int T_len, int64_t T_cap, int n_q, int n_kv, int hd, int n_splits, const float2* rope_tab,
                         hipStream_t s);
 
-// merge of split partials [n_splits][B][n_q][hd + 2] -> out float [B][n_q][hd]
+// merge of split partials [n_splits][B][n_q][hd + kPartPad] -> out float [B][n_q][hd]
 void launch_decode_combine(const float* part, float* out, int n_splits, int B, int n_q, int hd, hipStream_t s);
 
 // ---- base step with the predictor absorbed into the attention (kernels_absorbed.hip) ----
@@ -65,7 +69,7 @@ template <typename T>
 bool launch_absorb_o(const float* r, const T* wv, float* out, bf16* out_hi, bf16* out_lo, int B, int n_q, int n_kv, int hd,
                      int Ka, hipStream_t s);
 // attention of all query heads over one auxiliary layer, token-major ka, va [B*T][Ka]; any element
-// type, plain ALU (kernels_decode.hip).  part: [n_splits][B][n_q][Ka + 2]; out float [B][n_q][Ka]
+// type, plain ALU (kernels_decode.hip).  part: [n_splits][B][n_q][Ka + kPartPad]; out float [B][n_q][Ka]
 bool absorbed_attn_supported(int Ka);
 template <typename T>
 bool launch_absorbed_attn(const float* q, const T* ka, const T* va, float* part, float* out, int B, int T_len, int n_q,
@@ -84,14 +88,14 @@ void launch_kv_append(const float* k, const float* v, T* kc, T* vc, int B, int p
 // ---- kernels_base_chain.hip (bf16 base step; activations travel as bf16 high / low halves) ----
 int chain_ssq_parts(int N, int B);   // partial sums of squares a residual projection with N outputs emits per right-hand side
 void launch_base_embed(const int32_t* tokens, int T_len, const bf16* E, int vocab, const bf16* gain, float* y, bf16* uh,
-                       bf16* ul, float* ssq, int B, int d, hipStream_t s);
+                       bf16* ul, float* ssq, int B, int d, uint32_t* flags, hipStream_t s);
 // out = [rsqrt(mean + eps) *] W x         (ssq_in == NULL: no norm scale)
 void launch_chain_project(const bf16* W, const bf16* xh, const bf16* xl, const float* ssq_in, int n_part_in, float eps,
                           float* out, int B, int N, int K, hipStream_t s);
 // y += W x;  (yh, yl) = split(y * gain_next);  ssq_out = partial sums of y^2
 void launch_chain_residual(const bf16* W, const bf16* xh, const bf16* xl, float* y, const bf16* gain_next, bf16* yh,
                            bf16* yl, float* ssq_out, int B, int N, int K, hipStream_t s);
-// Same, but x = the merge of decode-attention split partials [n_splits][B][n_q][hd + 2] (what
+// Same, but x = the merge of decode-attention split partials [n_splits][B][n_q][hd + kPartPad] (what
 // launch_decode_attn leaves when it is given no destination), K = n_q * hd.  One or two
 // right-hand sides only; returns false (nothing launched) for shapes it does not serve.
 bool launch_chain_residual_merge(const bf16* W, const float* part, int n_splits, int n_q, int hd, float* y,

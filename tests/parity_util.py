@@ -11,11 +11,26 @@ from oracle import kvp_oracle as O
 # Tolerances of the benchmark spec: max |gpu - ref| / max |ref| per tensor slice
 # (one base layer's K^ or V^ of one sequence; one sequence's logits).
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
+# Second metric, asserted beside it: mean |gpu - ref| / mean |ref| per slice.  The maximum alone lets
+# any small element be wrong by 2 % of the slice's largest one (about 9 % of a typical element); the
+# mean cannot hide a systematic error in the small elements.  Bounds: float32 sums of <= 688 terms
+# stay below 1e-6 per element.  In bf16 mode every stored activation is rounded to 8 bits of mantissa
+# (relative error uniform in +-2^-9 at worst, rms about 1.6e-3); a full auxiliary layer rounds five of
+# them (normalised input, q/k/v, probabilities, attention output, SwiGLU product) into a float32
+# residual stream that adds them up like a random walk, and the predictor rounds its input and its
+# output once more: about 1.6e-3 * sqrt(5 L_A + 2) = 0.010 for 8 layers, 0.013 for 12 (measured at
+# the benchmark configurations: 0.008 - 0.0125).  Bounded at 2e-2, 1.5 to 2 times the estimate.
+TOL_MEAN = {"fp32": 1e-5, "bf16": 2e-2}
 
 
 def slice_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     denom = float(np.max(np.abs(ref)))
     return float(np.max(np.abs(got.astype(np.float64) - ref))) / max(denom, 1e-30)
+
+
+def slice_mean_err(got: np.ndarray, ref: np.ndarray) -> float:
+    denom = float(np.mean(np.abs(ref)))
+    return float(np.mean(np.abs(got.astype(np.float64) - ref))) / max(denom, 1e-30)
 
 
 def device_weights(cfg, store: S.WeightStore):
@@ -50,21 +65,26 @@ def run_gpu(cfg, store, tokens: np.ndarray, T_cap=None, stages=None, model=None)
 
 def compare(cfg, got, ref, tol=None, what=("K_hat", "V_hat", "logits")):
     """Returns the worst slice error per tensor and asserts the tolerance."""
+    tol_mean = TOL_MEAN[cfg.dtype] * (1.0 if tol is None else max(1.0, tol / TOL[cfg.dtype]))
     tol = TOL[cfg.dtype] if tol is None else tol
-    worst = {}
+    worst, worst_mean = {}, {}
     L, B = ref["K_hat"].shape[:2]
     for name in ("K_hat", "V_hat"):
         if name not in what:
             continue
-        w = 0.0
+        w = wm = 0.0
         for i in range(L):
             for b in range(B):
                 w = max(w, slice_rel_err(got[name][i, b], ref[name][i, b]))
-        worst[name] = w
+                wm = max(wm, slice_mean_err(got[name][i, b], ref[name][i, b]))
+        worst[name], worst_mean[name] = w, wm
     if "logits" in what and ref.get("logits") is not None:
         worst["logits"] = max(slice_rel_err(got["logits"][b], ref["logits"][b]) for b in range(B))
+        worst_mean["logits"] = max(slice_mean_err(got["logits"][b], ref["logits"][b]) for b in range(B))
     for k, v in worst.items():
         assert np.isfinite(v) and v <= tol, f"{cfg.name}: {k} worst slice error {v:.3e} > {tol:.1e} ({worst})"
+    for k, v in worst_mean.items():
+        assert np.isfinite(v) and v <= tol_mean, f"{cfg.name}: {k} worst slice-mean error {v:.3e} > {tol_mean:.1e} ({worst_mean})"
     return worst
 
 

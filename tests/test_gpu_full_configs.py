@@ -1,11 +1,21 @@
 """Parity at the benchmark configurations' full sizes, in the launch configuration bench.py
 times.  The GPU runs the whole batch; the fp64 oracle recomputes sampled sequences one by one
 (sequences are independent, so a sample is exact for what it covers):
-  * the whole path (K^, V^ at every layer and position, logits, first token) for `n_full` sequences;
-  * K^, V^ of a 192-token prefix of every other sequence (causality makes the prefix exact).
+  * the whole path (K^, V^ at every layer and position, logits, first token) for `n_full`
+    sequences -- by default every sequence of the batch (8 + 4 + 4 sequences over configurations
+    2 - 4); with fewer, the first and the last of the batch are always among them (the last one's
+    cache rows sit in the highest batch slot of every launch);
+  * K^, V^ of a 1024-token prefix of every other sequence (causality makes the prefix exact).
+Beside the slice-maximum error of the stated tolerance, a second metric is asserted per slice:
+mean |gpu - ref| / mean |ref|, which a few wrong small elements cannot hide behind a large maximum.
+The greedy first token must agree on every fully compared sequence, except that one sequence per
+configuration may differ when it is a near-tie (the oracle's two best logits closer than twice the
+observed logit error, the GPU's choice being the runner-up); each sequence is printed with the oracle's
+top-1 / top-2 margin and the observed logit error, and the agreement count is printed.
 Weights of the multi-billion-parameter shapes are drawn on the GPU (see kvp_synth)."""
 import os
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -13,15 +23,21 @@ import torch
 
 import kvp_synth as S
 from oracle import kvp_oracle as O
-from parity_util import TOL, slice_rel_err
+from parity_util import TOL, TOL_MEAN, slice_mean_err, slice_rel_err
 
 pytestmark = pytest.mark.gpu
 
+# fully compared sequences per configuration (KVP_TEST_FULL_SEQS overrides all three)
+N_FULL = {2: 8, 3: 4, 4: 4}
+PREFIX = 1024
 
-def _run_full(ci, n_full, prefix=192):
+
+def _run_full(ci, prefix=PREFIX):
     import paper_2410_08391_amd as K
     cfg = S.CONFIGS[ci]
     B, T = cfg.batch, cfg.seq_len
+    n_full = min(B, int(os.environ.get("KVP_TEST_FULL_SEQS", N_FULL[ci])))
+    full = sorted(set([0, B - 1][:n_full]) | set(range(1, n_full - 1)))     # first, last, then the ones after the first
     t0 = time.time()
     store = S.WeightStore(cfg, device="cuda" if cfg.gen_device == "cuda" else "cpu")
     names = S.hot_path_tensor_names(cfg)
@@ -31,47 +47,72 @@ def _run_full(ci, n_full, prefix=192):
     m = K.KVP(cfg, dev)
     m.run(torch.from_numpy(tok).to("cuda"))
     torch.cuda.synchronize()
-    print(f"\n{cfg.name}: weights + GPU run {time.time() - t0:.1f} s", flush=True)
+    print(f"\n{cfg.name}: weights + GPU run {time.time() - t0:.1f} s; full sequences {full}, "
+          f"{prefix}-token prefixes of the others", flush=True)
     kc, vc = m.caches(B)
-    tol = TOL[cfg.dtype]
-    worst = {"K_hat": 0.0, "V_hat": 0.0, "logits": 0.0}
-    agree = 0
-    for s in range(B):
+    logits_gpu = m.logits[:B].cpu().numpy()
+    first_gpu = m.argmax[:B].cpu().numpy()
+    tol, tol_mean = TOL[cfg.dtype], TOL_MEAN[cfg.dtype]
+
+    def oracle(s):
         t1 = time.time()
-        if s < n_full:
+        if s in full:
             ref = O.kvp_prefill_predict(cfg, store.f64, tok[s:s + 1])
-            Tc = T
         else:
             ref = O.kvp_prefill_predict(cfg, store.f64, tok[s:s + 1, :prefix], want_logits=False)
-            Tc = prefix
-        for name, cache in (("K_hat", kc), ("V_hat", vc)):
-            for i in range(cfg.base.n_layers):
-                got = cache[i, s, :, :Tc].float().cpu().numpy()
-                worst[name] = max(worst[name], slice_rel_err(got, ref[name][i, 0]))
-        if s < n_full:
-            got_l = m.logits[s].cpu().numpy()
-            worst["logits"] = max(worst["logits"], slice_rel_err(got_l, ref["logits"][0]))
-            first = int(m.argmax[s].item())
-            srt = np.sort(ref["logits"][0])
-            ok = first == int(ref["first"][0])
-            agree += ok
-            print(f"  seq {s}: first token gpu {first} oracle {int(ref['first'][0])} "
-                  f"(top-1/top-2 margin {srt[-1] - srt[-2]:.3f}, max |logit err| "
-                  f"{np.abs(got_l - ref['logits'][0]).max():.4f})", flush=True)
-        print(f"  seq {s}: oracle ({'full' if s < n_full else f'{prefix}-token prefix'}) {time.time() - t1:.1f} s, worst so far {worst}", flush=True)
+        return s, ref, time.time() - t1
+
+    worst = {"K_hat": 0.0, "V_hat": 0.0, "logits": 0.0}
+    worst_mean = {"K_hat": 0.0, "V_hat": 0.0, "logits": 0.0}
+    agree = 0
+    near_ties = []
+    # the oracle's element-wise passes are single-threaded: a few sequences side by side fill the host's cores
+    with ThreadPoolExecutor(max_workers=min(B, 4)) as ex:
+        for s, ref, secs in ex.map(oracle, range(B)):
+            Tc = T if s in full else prefix
+            for name, cache in (("K_hat", kc), ("V_hat", vc)):
+                for i in range(cfg.base.n_layers):
+                    got = cache[i, s, :, :Tc].float().cpu().numpy()
+                    worst[name] = max(worst[name], slice_rel_err(got, ref[name][i, 0]))
+                    worst_mean[name] = max(worst_mean[name], slice_mean_err(got, ref[name][i, 0]))
+            if s in full:
+                worst["logits"] = max(worst["logits"], slice_rel_err(logits_gpu[s], ref["logits"][0]))
+                worst_mean["logits"] = max(worst_mean["logits"], slice_mean_err(logits_gpu[s], ref["logits"][0]))
+                srt = np.sort(ref["logits"][0])
+                ok = int(first_gpu[s]) == int(ref["first"][0])
+                agree += ok
+                if not ok:
+                    # A different greedy token is accepted only as a near-tie: the oracle's two best logits closer
+                    # than twice the observed logit error, and the GPU's choice being the oracle's runner-up.
+                    lerr = float(np.abs(logits_gpu[s] - ref["logits"][0]).max())
+                    runner_up = int(np.argsort(ref["logits"][0])[-2])
+                    assert srt[-1] - srt[-2] <= 2 * lerr and int(first_gpu[s]) == runner_up, \
+                        f"{cfg.name} seq {s}: first token {int(first_gpu[s])} != oracle {int(ref['first'][0])} with margin " \
+                        f"{srt[-1] - srt[-2]:.4f} against a logit error of {lerr:.4f}"
+                    near_ties.append(s)
+                print(f"  seq {s}: first token gpu {int(first_gpu[s])} oracle {int(ref['first'][0])} "
+                      f"{'agree' if ok else 'MISMATCH'} (oracle top-1/top-2 margin {srt[-1] - srt[-2]:.3f}, max |logit err| "
+                      f"{np.abs(logits_gpu[s] - ref['logits'][0]).max():.4f})", flush=True)
+            print(f"  seq {s}: oracle ({'full' if s in full else f'{prefix}-token prefix'}) {secs:.1f} s; worst slice-max "
+                  f"{ {k: round(v, 5) for k, v in worst.items()} } worst slice-mean { {k: round(v, 5) for k, v in worst_mean.items()} }",
+                  flush=True)
+            del ref
+    print(f"{cfg.name}: greedy first token agrees on {agree}/{len(full)} fully compared sequences", flush=True)
     for k, v in worst.items():
-        assert np.isfinite(v) and v <= tol, f"{cfg.name}: {k} worst slice error {v:.3e} > {tol}"
-    assert agree == n_full, f"{cfg.name}: greedy first token agreed on {agree}/{n_full} sampled sequences"
+        assert np.isfinite(v) and v <= tol, f"{cfg.name}: {k} worst slice-max error {v:.3e} > {tol}"
+    for k, v in worst_mean.items():
+        assert np.isfinite(v) and v <= tol_mean, f"{cfg.name}: {k} worst slice-mean error {v:.3e} > {tol_mean}"
+    assert len(near_ties) <= 1, f"{cfg.name}: greedy first token differs on sequences {near_ties} (near-ties, but more than one)"
     m.close()
 
 
 def test_config2_full_size():
-    _run_full(2, n_full=int(os.environ.get("KVP_TEST_FULL_SEQS", "1")))
+    _run_full(2)
 
 
 def test_config3_full_size():
-    _run_full(3, n_full=int(os.environ.get("KVP_TEST_FULL_SEQS", "1")))
+    _run_full(3)
 
 
 def test_config4_full_size():
-    _run_full(4, n_full=int(os.environ.get("KVP_TEST_FULL_SEQS", "1")))
+    _run_full(4)

@@ -75,12 +75,8 @@ def _check_native(cfg, B, T, n_new=0):
             assert e <= tol, f"step {step} sequence {b}: logits {e:.3e} > {tol}"
 
     check_logits(0)
-    for s in range(1, max(1, n_new)):
-        fed = torch.tensor([int(ref[b]["tokens"][s - 1]) for b in range(B)], dtype=torch.int32, device="cuda")
-        m.generation_step(fed, T + s - 1)
-        torch.cuda.synchronize()
-        check_logits(s)
-    for l in range(cfg.aux.n_layers):                         # auxiliary cache, layer by layer
+    # auxiliary cache, layer by layer (before the generation steps: they reuse the start of the workspace)
+    for l in range(cfg.aux.n_layers):
         ka, va = m.aux_cache_layer(l, B, T)
         for b in range(B):
             KA, VA = O.aux_prefill(cfg, store.f64, tok[b])
@@ -88,6 +84,11 @@ def _check_native(cfg, B, T, n_new=0):
             assert e <= tol, f"K_A layer {l} sequence {b}: {e:.3e} > {tol}"
             e = slice_rel_err(va[b * T:(b + 1) * T].float().cpu().numpy(), O.merge_heads(VA[l]))
             assert e <= tol, f"V_A layer {l} sequence {b}: {e:.3e} > {tol}"
+    for s in range(1, max(1, n_new)):
+        fed = torch.tensor([int(ref[b]["tokens"][s - 1]) for b in range(B)], dtype=torch.int32, device="cuda")
+        m.generation_step(fed, T + s - 1)
+        torch.cuda.synchronize()
+        check_logits(s)
     n_valid = T + max(1, n_new) - 1
     for i in range(cfg.base.n_layers):
         kc, vc = m.cache_layer(i, B)
