@@ -21,7 +21,8 @@
  *   - Device memory: kvp_load_weights allocates the few small tables a handle owns (two rotary
  *     tables of max_seq x head_dim / 2 float2 each, one flag word, the predictor's pointer and
  *     layer-map tables) and kvp_free releases them.  No other call allocates or frees device
- *     memory: all per-call scratch comes in as `workspace`.
+ *     memory: all per-call scratch comes in as `workspace` (or, for kvp_generation_step_static,
+ *     lives in a static array inside the library).
  *   - Matrices are row-major [out_features, in_features] (y = W x), element type per
  *     kvp_config.dtype: float (KVP_DTYPE_F32) or bfloat16 (KVP_DTYPE_BF16).
  *   - Transformer block (fixed by the benchmark configurations, the paper only says
@@ -53,6 +54,9 @@ extern "C" {
 
 /* Bits of the device-side flag word, read with kvp_check_flags. */
 #define KVP_FLAG_TOKEN_CLAMPED 1u  /* a token id outside [0, vocab) was clamped into range */
+
+/* Size of the static scratch array behind kvp_generation_step_static (8 MiB per GPU). */
+#define KVP_STATIC_SCRATCH_BYTES (8u << 20)
 
 /* Stages of the path, for kvp_run_stages. */
 #define KVP_STAGE_AUX 1u       /* auxiliary prefill -> auxiliary cache in the workspace      */
@@ -264,6 +268,24 @@ int kvp_generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t
                         void* k_cache, void* v_cache, int64_t T_cap,
                         float* logits, int32_t* argmax,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* kvp_generation_step for callers that cannot allocate or pass scratch memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as kvp_generation_step, bit for bit, without the workspace: the scratch is a static
+ * device array of KVP_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on holds
+ * it until the process ends; its address on the handle's device is looked up by kvp_load_weights).
+ * The call allocates nothing, frees nothing, synchronises nothing and enqueues kernels only.
+ *   - KVP_ERR_WORKSPACE_TOO_SMALL when kvp_generation_workspace_bytes(h, B, pos + 1) exceeds
+ *     KVP_STATIC_SCRATCH_BYTES (the five benchmark configurations need 0.02 - 3.7 MB);
+ *   - KVP_ERR_BAD_CONFIG when the current device is not the one the handle was loaded on;
+ *   - KVP_ERR_BAD_SHAPE while the per-class timers are enabled (they create events).
+ * Every call on a GPU shares that GPU's array, whatever the handle: calls that overlap in time on
+ * one GPU (two streams, two handles, two threads) race on it.  Nothing in it has to start at zero:
+ * each kernel of the step writes what the next one reads. */
+size_t kvp_static_scratch_bytes(void);
+int kvp_generation_step_static(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos,
+                               void* k_cache, void* v_cache, int64_t T_cap,
+                               float* logits, int32_t* argmax, void* hip_stream);
 
 /* The workspace plan of a B x T call to kvp_prefill_predict / kvp_run_stages, for tests and
  * tools: every region the library carves out of the workspace, in address order.  Runs entirely on

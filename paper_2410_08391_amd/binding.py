@@ -19,7 +19,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 MODEL_BASE, MODEL_AUX = 0, 1
 EXPORTS = ("kvp_load_weights", "kvp_workspace_bytes", "kvp_prefill_predict", "kvp_run_stages",
            "kvp_aux_cache_offsets", "kvp_reference_workspace_bytes", "kvp_reference_prefill",
-           "kvp_generation_workspace_bytes", "kvp_generation_step", 
+           "kvp_generation_workspace_bytes", "kvp_generation_step", "kvp_generation_step_static", "kvp_static_scratch_bytes",
            "kvp_check_flags", "kvp_debug_plan", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
            "kvp_free", "kvp_last_error", "kvp_version")
 FLAG_TOKEN_CLAMPED = 1
@@ -93,6 +93,11 @@ def lib() -> C.CDLL:
     L.kvp_generation_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.kvp_generation_step.restype = C.c_int
+    L.kvp_generation_step_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
+    L.kvp_generation_step_static.restype = C.c_int
+    L.kvp_static_scratch_bytes.argtypes = []
+    L.kvp_static_scratch_bytes.restype = C.c_size_t
     L.kvp_check_flags.argtypes = [C.c_void_p, C.POINTER(C.c_uint32), C.c_int32]
     L.kvp_check_flags.restype = C.c_int
     L.kvp_debug_plan.argtypes = [C.POINTER(Config), C.c_int32, C.c_int32, C.POINTER(PlanRegion), C.c_int32,
@@ -250,6 +255,16 @@ def kvp_generation_step(handle: int, tokens, B: int, pos: int, k_cache, v_cache,
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().kvp_generation_step(handle, _ptr(tokens), B, pos, _ptr(k_cache), _ptr(v_cache), T_cap,
                                      _ptr(logits), _ptr(argmax), _ptr(workspace), ws_bytes, stream))
+
+
+def kvp_generation_step_static(handle: int, tokens, B: int, pos: int, k_cache, v_cache, T_cap: int, logits, argmax,
+                               stream: int = 0) -> None:
+    _check(lib().kvp_generation_step_static(handle, _ptr(tokens), B, pos, _ptr(k_cache), _ptr(v_cache), T_cap,
+                                            _ptr(logits), _ptr(argmax), stream))
+
+
+def kvp_static_scratch_bytes() -> int:
+    return int(lib().kvp_static_scratch_bytes())
 
 
 def kvp_check_flags(handle: int, clear: bool = False) -> int:

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -21,6 +22,30 @@ using namespace kvp;
 namespace {
 
 thread_local char g_err[512] = "";
+
+// Scratch of kvp_generation_step_static: device memory that is part of the library's code object, so a
+// caller that may not allocate (HIP graph capture, a serving loop that forbids it) needs no workspace.
+// Every GPU the library runs on holds its own copy until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: the per-device address is looked up once per device in
+// kvp_load_weights and kept in g_scratch_ptr; kernels are always given that address, never the name.
+static __device__ __align__(256) unsigned char scratch[KVP_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Address of the static scratch array on the current device (looked up on first use per device).
+hipError_t scratch_address(int device, void** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -906,6 +931,10 @@ int kvp_load_weights(const kvp_config* cfg, const kvp_weights* wts, kvp_handle**
   launch_rope_table(h->rope_base, cfg->max_seq, cfg->base.head_dim / 2, (double)cfg->rope_theta, nullptr);
   e = hipDeviceSynchronize();
   if (e != hipSuccess) { kvp_free(h); return fail(KVP_ERR_HIP, "rotary table kernel: %s", hipGetErrorString(e)); }
+  // address of the static scratch array on this device, for kvp_generation_step_static (which may not look it up itself)
+  void* sp = nullptr;
+  e = scratch_address(h->device, &sp);
+  if (e != hipSuccess) { kvp_free(h); return fail(KVP_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e)); }
   const char* no_ov = getenv("KVP_NO_OVERLAP");
   if (h->use_mfma && !(no_ov && no_ov[0] == '1')) {
     // default priority, no implicit synchronisation with the legacy default stream
@@ -1064,7 +1093,8 @@ size_t kvp_generation_workspace_bytes(const kvp_handle* h, int32_t B, int32_t T_
   return plan_workspace(h, B, T_total, true).total;
 }
 
-// Body of kvp_generation_step: `scratch_bytes` of device scratch at `scratch_mem`.
+// Shared body of kvp_generation_step and kvp_generation_step_static: `scratch_bytes` of device scratch at
+// `scratch_mem`, from the caller's workspace or from the library's static array.
 static int generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos, void* k_cache, void* v_cache,
                            int64_t T_cap, float* logits, int32_t* argmax, void* scratch_mem, size_t scratch_bytes,
                            const char* scratch_name, void* hip_stream) {
@@ -1106,6 +1136,33 @@ int kvp_generation_step(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t
   if (!workspace) return fail(KVP_ERR_NULL, "workspace is NULL");
   return generation_step(h, tokens, B, pos, k_cache, v_cache, T_cap, logits, argmax, workspace, workspace_bytes, "workspace",
                          hip_stream);
+}
+
+size_t kvp_static_scratch_bytes(void) { return KVP_STATIC_SCRATCH_BYTES; }
+
+int kvp_generation_step_static(kvp_handle* h, const int32_t* tokens, int32_t B, int32_t pos, void* k_cache, void* v_cache,
+                               int64_t T_cap, float* logits, int32_t* argmax, void* hip_stream) {
+  if (!h) return fail(KVP_ERR_NULL, "handle is NULL");
+  if (h->prof_on) return fail(KVP_ERR_BAD_SHAPE, "kvp_generation_step_static: the per-class timers create events; disable them first");
+  // The per-device address was looked up by kvp_load_weights; nothing is looked up or allocated here.
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+    return fail(KVP_ERR_BAD_CONFIG, "kvp_generation_step_static: current device %d is not the handle's device %d", dev, h->device);
+  void* sp = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    sp = g_scratch_ptr[dev];
+  }
+  if (!sp) return fail(KVP_ERR_HIP, "kvp_generation_step_static: the scratch array's address is unknown on device %d", dev);
+  if (B >= 1 && B <= h->cfg.max_batch && pos >= 1 && pos + 1 <= h->cfg.max_seq) {
+    const size_t need = plan_workspace(h, B, pos + 1, true).total;
+    if (need > KVP_STATIC_SCRATCH_BYTES)
+      return fail(KVP_ERR_WORKSPACE_TOO_SMALL, "kvp_generation_step_static: B = %d at %d cache entries needs %zu bytes of scratch, "
+                  "the static array holds %zu; use kvp_generation_step with a workspace", B, pos + 1, need,
+                  (size_t)KVP_STATIC_SCRATCH_BYTES);
+  }
+  return generation_step(h, tokens, B, pos, k_cache, v_cache, T_cap, logits, argmax, sp, KVP_STATIC_SCRATCH_BYTES,
+                         "static scratch", hip_stream);
 }
 
 int kvp_profile_enable(kvp_handle* h, int32_t on) {
