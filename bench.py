@@ -3,10 +3,15 @@
 
 A step is one pass of the whole path (auxiliary prefill -> predictor -> one base step ->
 greedy first token) over one batch of synthetic prompts, inputs resident in HBM.
-Prints ONE JSON line: TTFT (ms_per_step), prompt tokens/s (value), the roofline of the
-dominant kernel class, all per-class rooflines, and the CPU oracle timed beside it.
+Prints ONE JSON line: TTFT (ms_per_step: each step is one call, timed from before the call
+to its first tokens on the host), prompt tokens/s (value), the roofline of the dominant kernel
+class, all per-class rooflines, the chip's achievable peaks measured by plain probe kernels,
+and the CPU oracle timed beside it.  Without --config the workload is the largest benchmark
+configuration (config 4: 8B-class base, batch 4, 8192-token prompts).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+
+    python bench.py --peaks                   # only the achievable-peak probes
 
     python bench.py --sweep --config 2        # the three systems over prompt lengths at batch 8
 
@@ -18,6 +23,7 @@ alone) to its first token: the two reference points of the paper's timing experi
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -119,20 +125,42 @@ def roofline_entry(work, ms, launches, dtype):
     return e
 
 
-def load_traffic():
-    """Measured HBM traffic per kernel class in bytes per step (two rocprofv3 --pmc runs, FETCH_SIZE
-    and WRITE_SIZE, each scaled by what the counter reads for a 256 MiB device copy; summarised
-    under profiles/); absent entries stay null."""
+def kernel_sources_sha256():
+    """Fingerprint of the kernel sources (every file under csrc/, in name order): measured traffic
+    figures are only quoted while the kernels they were measured on are the ones that run."""
+    d = os.path.join(ROOT, "paper_2410_08391_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()
+
+
+def load_traffic(workload):
+    """Measured HBM traffic per kernel class in bytes per step for `workload` (two rocprofv3 --pmc
+    runs, FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a 256 MiB device
+    copy; summarised under profiles/).  Each entry of profiles/traffic.json carries the fingerprint
+    of the kernel sources it was measured on; an entry measured on other sources is stale and is
+    not quoted.  Returns (bytes per class, note)."""
     p = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(p):
-        with open(p) as f:
-            return json.load(f)
-    return {}
+    if not os.path.exists(p):
+        return {}, "no profiles/traffic.json"
+    with open(p) as f:
+        data = json.load(f)
+    if workload not in data:
+        return {}, "not measured for this workload"
+    stamp = data.get(workload + "__sources_sha256")
+    if stamp != kernel_sources_sha256():
+        return {}, "stale: measured on other kernel sources (sha256 %s...)" % (stamp or "unstamped")[:12]
+    return data[workload], "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"
 
 
-def cpu_baseline(cfg, store, tokens, budget_s=30.0):
-    """The CPU oracle as it stands, on a bounded sample of the same workload."""
-    import numpy as np
+def cpu_baseline(cfg, store, tokens):
+    """The CPU oracle as it stands, on a bounded sample of the same workload: ONE WHOLE sequence
+    of the batch (sequences are independent, so a whole sequence is exact for what it covers;
+    a prefix would flatter the oracle on long prompts, attention being quadratic)."""
     from oracle import kvp_oracle as O
     try:
         from threadpoolctl import threadpool_info
@@ -140,16 +168,47 @@ def cpu_baseline(cfg, store, tokens, budget_s=30.0):
     except Exception:
         cores = len(os.sched_getaffinity(0))
     B, T = tokens.shape
-    # cost grows ~linearly in tokens (plus attention): cut the sample to one sequence and, for
-    # long prompts, to a prefix, keeping about 10-30 s of CPU work
-    t_sample = T if T <= 1024 else 1024
-    sample = tokens[:1, :t_sample]
+    sample = tokens[:1]
     t0 = time.time()
     O.kvp_prefill_predict(cfg, store.f64, sample)
     dt = time.time() - t0
-    return {"value": t_sample / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 sequence x {t_sample} tokens of the workload ({B} x {T}), whole path incl. base step, {dt:.1f} s",
+    return {"value": T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 whole sequence of {T} tokens out of the workload's {B} x {T}, whole path incl. base step, {dt:.1f} s",
             "seconds": dt}
+
+
+def achievable_peaks(K, torch, nbytes=1 << 30, reps=5):
+    """What the chip sustains on the two roofs, from the library's probe kernels (kernels_probe.hip):
+    a register-resident bf16 MFMA loop, a streaming read, a copy and a fill over 1 GiB, each the best
+    of `reps` launches timed with HIP events on the launch stream."""
+    stream = torch.cuda.current_stream()
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    a.random_(0, 256)
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+
+    def best(fn):
+        t = []
+        for _ in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            t.append(e0.elapsed_time(e1))
+        return min(t[1:])
+
+    flops = [0.0]
+    def mfma():
+        flops[0] = K.kvp_probe_mfma(sink, 20000, stream.cuda_stream)
+    ms = best(mfma)
+    out = {"mfma_bf16_tflops": flops[0] / (ms / 1e3) / 1e12, "mfma_probe_ms": ms}
+    out["read_gbs"] = nbytes / (best(lambda: K.kvp_probe_stream(0, a, b, nbytes, stream.cuda_stream)) / 1e3) / 1e9
+    out["copy_gbs"] = 2 * nbytes / (best(lambda: K.kvp_probe_stream(1, a, b, nbytes, stream.cuda_stream)) / 1e3) / 1e9
+    out["fill_gbs"] = nbytes / (best(lambda: K.kvp_probe_stream(2, a, b, nbytes, stream.cuda_stream)) / 1e3) / 1e9
+    out["note"] = ("probe kernels of the library: register-resident v_mfma_f32_32x32x16_bf16 loop (no memory traffic); "
+                   "streaming read / copy (read + written bytes) / fill over 1 GiB")
+    return out
 
 
 def reference_main(args):
@@ -290,10 +349,13 @@ def sweep_main(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4,
+                    help="benchmark configuration 0..4 (default 4: the largest, 8B-class base, batch 4, 8192-token prompts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--peaks", action="store_true", help="run only the achievable-peak probes and print them as one JSON line")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-peak probes")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run one plain 256 MiB device copy, so a rocprofv3 --pmc run of this command "
                          "holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -330,6 +392,11 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.peaks:
+        print(json.dumps({"metric": "achievable peaks (probe kernels)", "n_gpus": 1, "data": "synthetic",
+                          "published": {"mfma_bf16_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
+                          "achievable": achievable_peaks(K, torch)}))
+        return
     cfg = S.CONFIGS[args.config]
     if args.layerwise:
         cfg = layerwise_variant(cfg)
@@ -347,25 +414,30 @@ def main():
     for _ in range(args.warmup):
         m.run(tok)
     torch.cuda.synchronize()
+    # The timed region: K steps, each ONE call as a caller sees it -- from just before the call to after
+    # the stream has drained and the first tokens are on the host.  ms_per_step is the mean over the K
+    # steps (the region is bracketed by synchronisation on both sides), ttft_ms their median.
+    lat = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t1 = time.perf_counter()
+        m.run(tok)
+        first = m.argmax[:B].cpu().tolist()          # blocks until the call's work is done
+        lat.append((time.perf_counter() - t1) * 1e3)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    lat.sort()
+    pct = lambda q: lat[min(len(lat) - 1, int(q * len(lat)))]
+    ttft = pct(0.50)
+
+    # For comparison: the same K calls queued back to back (the host's launch work of call i+1 hides
+    # behind the device work of call i); not what a single caller sees, so not the headline.
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         m.run(tok)
     torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    first = m.argmax[:B].cpu().tolist()
-
-    # Time to first token as one caller sees it: each call on its own, from just before the call to after
-    # the stream has drained and the first tokens are on the host (the K calls above are pipelined on the stream
-    # and amortise the host's launch work; these are not).
-    lat = []
-    for _ in range(args.steps):
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        m.run(tok)
-        _ = m.argmax[:B].cpu()
-        lat.append((time.perf_counter() - t1) * 1e3)
-    lat.sort()
-    pct = lambda q: lat[min(len(lat) - 1, int(q * len(lat)))]
+    ms_pipelined = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # Device time per stage: one HIP event between the stages, on the stream the kernels run on
     # (three events per step perturb nothing measurable).
@@ -398,7 +470,7 @@ def main():
                 for c in stage_of}
 
     work = algorithmic_work(cfg, B, T)
-    traffic = load_traffic().get(workload_name(cfg, B, T), {})
+    traffic, traffic_note = load_traffic(workload_name(cfg, B, T))
     roofs = {}
     for cls, wk in work.items():
         e = roofline_entry(wk, class_ms[cls], prof[cls]["launches"] / args.steps, cfg.dtype)
@@ -416,7 +488,7 @@ def main():
         "metric": "prompt_tokens_per_s (TTFT path: aux prefill + KV predictor + 1 base step)",
         "value": B * T / (ms / 1e3),
         "unit": "tokens/s",
-        "ttft_ms": ms,
+        "ttft_ms": ttft,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -424,10 +496,14 @@ def main():
                    "path": "mfma" if cfg.dtype == "bf16" else "fp32", "first_tokens": first[:8]},
         "roofline": roof,
         "rooflines": roofs,
-        "ttft_single_call_ms": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90),
-                                "note": "one call at a time: host wall time from before the call to first tokens on the host"},
-        "ttft_note": "ms_per_step is the whole path as the library schedules it (auxiliary chain and predictor + base "
-                     "chain overlapped on two streams); stage_ms are the stages run one after another",
+        "ttft_single_call_ms": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90), "mean": ms,
+                                "note": "the timed steps: one call at a time, host wall time from before the call to first tokens on the host"},
+        "pipelined_ms_per_step": ms_pipelined,
+        "ttft_note": "ms_per_step / value: mean of the K timed steps, each a single call of the whole path as the library "
+                     "schedules it (auxiliary chain and predictor + base chain overlapped on two streams) up to its first "
+                     "tokens on the host; ttft_ms: their median; pipelined_ms_per_step: K calls queued back to back; "
+                     "stage_ms: the stages run one after another",
+        "traffic_note": traffic_note,
         "stage_ms": stage_ms,
         "event_chain_ms_sum": sum(prof[c]["ms"] for c in prof) / args.steps,
     }
@@ -485,6 +561,14 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         out["pmc_calibration"] = {"kernel": "torch device copy", "bytes_read": 256 * 1024 * 1024, "bytes_written": 256 * 1024 * 1024}
+    if not args.no_peaks:
+        del m
+        torch.cuda.empty_cache()
+        out["achievable"] = achievable_peaks(K, torch)
+        ach = out["achievable"]
+        for e in list(roofs.values()) + [roof]:       # every fraction also against the measured peak
+            e["frac_of_achievable"] = e["achieved"] / (ach["read_gbs"] if e["bound"] == "hbm" else ach["mfma_bf16_tflops"]) \
+                if cfg.dtype == "bf16" or e["bound"] == "hbm" else None
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, store, tokens)
     print(json.dumps(out))

@@ -304,6 +304,19 @@ typedef struct {
 int kvp_debug_plan(const kvp_config* cfg, int32_t B, int32_t T, kvp_plan_region* regions, int32_t capacity,
                    int32_t* n_regions, uint64_t* total_bytes);
 
+/* Achievable-peak probes (measurement aids, not part of the path): plain kernels of known work
+ * whose rate is what this chip sustains on the two roofs the path's kernels are priced against.
+ * Both only enqueue one kernel on hip_stream; the caller times it (HIP events on that stream).
+ * kvp_probe_mfma: a register-resident loop of the matrix-core instruction all GEMM and attention
+ *   kernels here use (v_mfma_f32_32x32x16_bf16), no memory traffic; *flops_out (host) receives the
+ *   floating-point operations the launch performs; sink: device, >= 4 bytes, never written in
+ *   practice.
+ * kvp_probe_stream: kind 0 reads `bytes` from src, 1 copies src -> dst, 2 fills dst; src / dst
+ *   device, 16-byte aligned, `bytes` long (kind 0 writes nothing but needs dst != NULL).
+ * Errors: KVP_ERR_NULL, KVP_ERR_BAD_SHAPE, KVP_ERR_HIP (kvp_last_error is not set). */
+int kvp_probe_mfma(float* sink, int32_t iters, double* flops_out, void* hip_stream);
+int kvp_probe_stream(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream);
+
 /* Per-kernel-class timers.  While enabled, one HIP event is recorded on the caller's stream after
  * every launch (a decode-attention split + merge pair counts as one); the time between consecutive
  * events is charged to the class of the later launch (this perturbs end-to-end time a little: use

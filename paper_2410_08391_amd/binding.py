@@ -20,7 +20,7 @@ MODEL_BASE, MODEL_AUX = 0, 1
 EXPORTS = ("kvp_load_weights", "kvp_workspace_bytes", "kvp_prefill_predict", "kvp_run_stages",
            "kvp_aux_cache_offsets", "kvp_reference_workspace_bytes", "kvp_reference_prefill",
            "kvp_generation_workspace_bytes", "kvp_generation_step", "kvp_generation_step_static", "kvp_static_scratch_bytes",
-           "kvp_check_flags", "kvp_debug_plan", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
+           "kvp_check_flags", "kvp_debug_plan", "kvp_probe_mfma", "kvp_probe_stream", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
            "kvp_free", "kvp_last_error", "kvp_version")
 FLAG_TOKEN_CLAMPED = 1
 
@@ -103,6 +103,10 @@ def lib() -> C.CDLL:
     L.kvp_debug_plan.argtypes = [C.POINTER(Config), C.c_int32, C.c_int32, C.POINTER(PlanRegion), C.c_int32,
                                  C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
     L.kvp_debug_plan.restype = C.c_int
+    L.kvp_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+    L.kvp_probe_mfma.restype = C.c_int
+    L.kvp_probe_stream.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.kvp_probe_stream.restype = C.c_int
     L.kvp_aux_cache_offsets.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     L.kvp_aux_cache_offsets.restype = C.c_int
     L.kvp_profile_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -271,6 +275,22 @@ def kvp_check_flags(handle: int, clear: bool = False) -> int:
     v = C.c_uint32()
     _check(lib().kvp_check_flags(handle, C.byref(v), 1 if clear else 0))
     return int(v.value)
+
+
+def kvp_probe_mfma(sink, iters: int, stream: int = 0) -> float:
+    """Enqueues the matrix-core probe; returns the floating-point operations it performs."""
+    f = C.c_double()
+    rc = lib().kvp_probe_mfma(_ptr(sink), iters, C.byref(f), stream)
+    if rc != 0:
+        raise KVPError(rc, "kvp_probe_mfma")
+    return float(f.value)
+
+
+def kvp_probe_stream(kind: int, src, dst, nbytes: int, stream: int = 0) -> None:
+    """Enqueues a streaming probe over nbytes: kind 0 read src, 1 copy src -> dst, 2 fill dst."""
+    rc = lib().kvp_probe_stream(kind, _ptr(src), _ptr(dst), nbytes, stream)
+    if rc != 0:
+        raise KVPError(rc, "kvp_probe_stream")
 
 
 def kvp_free(handle: int) -> None:

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libkvp.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 SOURCES = ["kvp_api.hip", "kernels_generic.hip", "kernels_decode.hip", "kernels_base_chain.hip", "kernels_mfma.hip",
-           "kernels_absorbed.hip", "kernels_predictor.hip"]
+           "kernels_absorbed.hip", "kernels_predictor.hip", "kernels_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -1,0 +1,98 @@
+// Achievable-peak probes: what this chip sustains on the two roofs the path's kernels are priced
+// against, measured by plain kernels of known work.  Measurement aids behind the C ABI
+// (kvp_probe_mfma, kvp_probe_stream); no step of the path uses them.
+//   * matrix cores: a register-resident loop of v_mfma_f32_32x32x16_bf16 (the instruction every GEMM
+//     and attention kernel of the library issues), eight independent accumulators per wave, two
+//     waves per SIMD, no memory traffic at all -- the rate the pipes reach at the clock the chip
+//     holds under full matrix load;
+//   * HBM: a streaming read, a copy and a fill over a caller-supplied buffer, 16 bytes per lane and
+//     access, four accesses in flight per thread.
+#include <hip/hip_runtime.h>
+
+#include "../../include/kvp.h"
+#include "common.h"
+
+namespace kvp {
+
+constexpr int PROBE_ACCS = 8;             // independent accumulators per wave
+constexpr int PROBE_MFMA_BLOCKS = 2048;   // 256 CUs x 8 blocks of 4 waves: every SIMD holds waves throughout
+
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters) {
+  const int lane = threadIdx.x % kWave;
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {           // small, lane-dependent operands: sums stay far from overflow
+    a[i] = (bf16)(0.001f * (float)((lane * 7 + i * 3) % 13 - 6));
+    b[i] = (bf16)(0.001f * (float)((lane * 5 + i) % 11 - 5));
+  }
+  f32x16 acc[PROBE_ACCS];
+#pragma unroll
+  for (int j = 0; j < PROBE_ACCS; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < PROBE_ACCS; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < PROBE_ACCS; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[j][i];
+  if (s == 123456.789f) sink[0] = s;      // keeps the loop alive; the comparison never holds
+}
+
+// kind 0: read src;  1: copy src -> dst;  2: fill dst.  n16: number of 16-byte pieces.
+template <int KIND>
+__global__ __launch_bounds__(256) void probe_stream_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16,
+                                                           uint32_t* __restrict__ sink) {
+  constexpr int U = 4;
+  const size_t stride = (size_t)gridDim.x * 256;
+  uint32_t x = 0;
+  for (size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x; i0 < n16; i0 += U * stride) {
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = i0 + u * stride;
+      if (KIND != 2) v[u] = src[i < n16 ? i : i0];
+      else v[u] = uint4{(uint32_t)i, 1u, 2u, 3u};
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t i = i0 + u * stride;
+      if (KIND == 0) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+      else if (i < n16) dst[i] = v[u];
+    }
+  }
+  if (KIND == 0 && x == 0x9e3779b9u && src[0].x == 0x7f4a7c15u) sink[0] = x;   // practically never; keeps the loads alive
+}
+
+}  // namespace kvp
+
+using namespace kvp;
+
+extern "C" {
+
+int kvp_probe_mfma(float* sink, int32_t iters, double* flops_out, void* hip_stream) {
+  if (!sink || !flops_out || iters < 1) return KVP_ERR_NULL;
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(PROBE_MFMA_BLOCKS), dim3(256), 0, (hipStream_t)hip_stream, sink, iters);
+  // blocks x 4 waves x iterations x accumulators x (32 x 32 x 16 multiply-adds)
+  *flops_out = (double)PROBE_MFMA_BLOCKS * 4.0 * (double)iters * PROBE_ACCS * (2.0 * 32 * 32 * 16);
+  return hipGetLastError() == hipSuccess ? KVP_OK : KVP_ERR_HIP;
+}
+
+int kvp_probe_stream(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (kind < 0 || kind > 2 || (kind != 2 && !src) || !dst || bytes < 16) return KVP_ERR_NULL;
+  if (((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return KVP_ERR_BAD_SHAPE;
+  const size_t n16 = bytes / 16;
+  const dim3 grid(4096), block(256);
+  hipStream_t s = (hipStream_t)hip_stream;
+  const uint4* sp = (const uint4*)src;
+  uint4* dp = (uint4*)dst;
+  if (kind == 0) hipLaunchKernelGGL((probe_stream_kernel<0>), grid, block, 0, s, sp, dp, n16, (uint32_t*)dst);
+  else if (kind == 1) hipLaunchKernelGGL((probe_stream_kernel<1>), grid, block, 0, s, sp, dp, n16, (uint32_t*)nullptr);
+  else hipLaunchKernelGGL((probe_stream_kernel<2>), grid, block, 0, s, sp, dp, n16, (uint32_t*)nullptr);
+  return hipGetLastError() == hipSuccess ? KVP_OK : KVP_ERR_HIP;
+}
+
+}  // extern "C"

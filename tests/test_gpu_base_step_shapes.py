@@ -43,3 +43,14 @@ def test_generation_wide_base_model():
     """Generation loop (own key / value projections on the same kernels) at K = 2048 / 2176, five sequences."""
     cfg = S.tiny_config("bf16", base=(2, 2048, 16, 4, 128, 2176), aux=AUX, batch=5, seq_len=40, vocab=4112, seed=127)
     _generate(cfg, 3)
+
+
+@pytest.mark.parametrize("B,T", [(3, 500), (4, 700), (8, 300), (5, 1100), (16, 600)])
+def test_chain_kernels_with_several_attention_splits(B, T):
+    """Three to sixteen sequences at prompt lengths that give the decode attention 5 to 18 splits per
+    (sequence, kv head): split kernel + combine launch feeding the matrix-core output projection."""
+    cfg = S.tiny_config("bf16", base=(2, 2048, 16, 4, 128, 2176), aux=AUX, batch=B, seq_len=T, vocab=1000, seed=131 + B)
+    store = S.WeightStore(cfg)
+    tok = S.draw_tokens(cfg)
+    got = run_gpu(cfg, store, tok)
+    compare(cfg, got, O.kvp_prefill_predict(cfg, store.f64, tok))

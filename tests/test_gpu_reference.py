@@ -28,22 +28,34 @@ def _run(cfg, side, tokens, keep_cache=True, env=None):
     return got, ref
 
 
-def _compare(cfg, got, ref):
+def _compare(cfg, got, ref, show=False):
     # The 2e-2 (bf16) / 1e-4 (fp32) bound is stated for the predicted cache, which sits behind
     # auxiliary stacks of 8 to 12 layers.  Every layer adds independent roundings of the same size
     # to the residual stream (h, q, k, v, P, attention output, SwiGLU activation), so the error of
-    # a deeper stack grows like a random walk: the bound scales with sqrt(layers / 8).
+    # a deeper stack grows like a random walk: the bound scales with sqrt(layers / 8).  The exponent
+    # is measured, not assumed: `show` prints the worst slice error of every layer's keys and values
+    # (configuration 1's 28-layer base model: the design notes hold the table and the fitted exponent).
     L, B = ref["K"].shape[:2]
     tol = TOL[cfg.dtype] * max(1.0, float(np.sqrt(L / 8.0)))
-    for name in ("K", "V"):
-        if name in got:
-            for i in range(L):
+    per_layer = []
+    for i in range(L):
+        worst = 0.0
+        for name in ("K", "V"):
+            if name in got:
                 for b in range(B):
                     e = slice_rel_err(got[name][i, b], ref[name][i, b])
                     assert e <= tol, f"{name} layer {i} sequence {b}: {e:.3e} > {tol}"
+                    worst = max(worst, e)
+        per_layer.append(worst)
     for b in range(B):
         e = slice_rel_err(got["logits"][b], ref["logits"][b])
         assert e <= tol, f"logits sequence {b}: {e:.3e} > {tol}"
+    if show and "K" in got:
+        print("\nworst K/V slice error by layer (1-based depth): " + " ".join(f"{i + 1}:{e:.4f}" for i, e in enumerate(per_layer)))
+        d = np.arange(2, L + 1, dtype=np.float64)          # layer 1's keys carry no accumulated residual error yet
+        slope = np.polyfit(np.log(d), np.log(np.asarray(per_layer[1:])), 1)[0]
+        print(f"fitted exponent of error ~ depth^p over layers 2..{L}: p = {slope:.2f} (bound used: {tol:.3e} = {TOL[cfg.dtype]} * sqrt({L}/8))")
+    return per_layer
 
 
 @pytest.mark.parametrize("side", ["base", "aux"])
@@ -84,7 +96,7 @@ def test_reference_prefill_config1_base():
     cfg = S.CONFIGS[1]
     tok = S.draw_tokens(cfg)
     got, ref = _run(cfg, "base", tok)
-    _compare(cfg, got, ref)
+    _compare(cfg, got, ref, show=True)
 
 
 def test_reference_prefill_identity_relation():
