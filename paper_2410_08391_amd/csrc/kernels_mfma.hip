@@ -190,7 +190,6 @@ static void launch_gemm(const bf16* A, int lda, int M, int Nv, int K, int batche
 static int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 typedef GemmTile<256, 256, 2, 4, 2> TileBig;     // 8 waves (two per SIMD), 128x64 per wave, 2 stages of 64 KB
-typedef GemmTile<256, 256, 2, 2, 2> TileBig4;    // 4 waves (one per SIMD), 128x128 per wave: 0.5 LDS fragment reads per MFMA instead of 0.75
 typedef GemmTile<128, 128, 4, 2, 4> TileSmall;   // 8 waves, 32x64 per wave, 4 stages of 32 KB: one block per CU, deep pipeline
 typedef GemmTile<128, 128, 4, 2, 2> TileSmall2;  // same tile, 2 stages: two blocks per CU, for grids larger than the chip
 typedef GemmTile<128, 64, 4, 1, 3> TileNarrow;   // 4 waves, 32x64 per wave, 3 stages of 24 KB: two blocks per CU
@@ -198,11 +197,10 @@ typedef GemmTile<128, 64, 4, 1, 3> TileNarrow;   // 4 waves, 32x64 per wave, 3 s
 // Tile choice: the biggest tile whose grid still fills the 256 CUs; small problems (few thousand
 // tokens) are bound by how many K steps a block runs back to back, so they get smaller tiles,
 // more blocks and a deeper load pipeline.
-enum TileKind { TILE_BIG, TILE_SMALL, TILE_SMALL2, TILE_NARROW, TILE_BIG4 };
+enum TileKind { TILE_BIG, TILE_SMALL, TILE_SMALL2, TILE_NARROW };
 static TileKind pick_tile(int M, int Nv, bool narrow_ok, int batches = 1) {
   const char* force = getenv("KVP_GEMM_TILE");      // "big" / "small" / "narrow": for tests and tuning
   if (force && force[0] == 'b') return TILE_BIG;
-  if (force && force[0] == 'w') return TILE_BIG4;
   if (force && force[0] == 's') return (force[1] == '2') ? TILE_SMALL2 : TILE_SMALL;
   if (force && force[0] == 'n' && narrow_ok) return TILE_NARROW;
   long big = (long)((M + 255) / 256) * ((Nv + 255) / 256);
@@ -224,7 +222,6 @@ static TileKind pick_tile(int M, int Nv, bool narrow_ok, int batches = 1) {
 void mfma_gemm_residual(const bf16* A, const bf16* W, float* X, int M, int N, int K, hipStream_t s) {
   switch (pick_tile(M, N, true)) {
     case TILE_BIG: launch_gemm<TileBig>(A, K, M, N, K, 1, BPlain<256>{W, N, K}, EpiResidualPair<256>{X, N}, s); break;
-    case TILE_BIG4: launch_gemm<TileBig4>(A, K, M, N, K, 1, BPlain<256>{W, N, K}, EpiResidualPair<256>{X, N}, s); break;
     case TILE_SMALL: launch_gemm<TileSmall>(A, K, M, N, K, 1, BPlain<128>{W, N, K}, EpiResidualPair<128>{X, N}, s); break;
     case TILE_SMALL2: launch_gemm<TileSmall2>(A, K, M, N, K, 1, BPlain<128>{W, N, K}, EpiResidualPair<128>{X, N}, s); break;
     default: launch_gemm<TileNarrow>(A, K, M, N, K, 1, BPlain<64>{W, N, K}, EpiResidualPair<64>{X, N}, s); break;
@@ -234,7 +231,6 @@ void mfma_gemm_residual(const bf16* A, const bf16* W, float* X, int M, int N, in
 void mfma_gemm_swiglu(const bf16* A, const bf16* Wg, const bf16* Wu, bf16* act, int M, int F, int K, hipStream_t s) {
   switch (pick_tile(M, 2 * F, true)) {
     case TILE_BIG: launch_gemm<TileBig>(A, K, M, 2 * F, K, 1, BGateUp<256>{Wg, Wu, F, K}, EpiSwiGLU<256>{act, F}, s); break;
-    case TILE_BIG4: launch_gemm<TileBig4>(A, K, M, 2 * F, K, 1, BGateUp<256>{Wg, Wu, F, K}, EpiSwiGLU<256>{act, F}, s); break;
     case TILE_SMALL: launch_gemm<TileSmall>(A, K, M, 2 * F, K, 1, BGateUp<128>{Wg, Wu, F, K}, EpiSwiGLU<128>{act, F}, s); break;
     case TILE_SMALL2: launch_gemm<TileSmall2>(A, K, M, 2 * F, K, 1, BGateUp<128>{Wg, Wu, F, K}, EpiSwiGLU<128>{act, F}, s); break;
     default: launch_gemm<TileNarrow>(A, K, M, 2 * F, K, 1, BGateUp<64>{Wg, Wu, F, K}, EpiSwiGLU<64>{act, F}, s); break;
@@ -274,10 +270,7 @@ void mfma_qkv_rope(const bf16* hbuf, const bf16* wq, const bf16* wk, const bf16*
   int heads = n_q + 2 * n_kv - head0;
   const int rot = rotate ? n_q + n_kv : 0;
   TileKind kind = pick_tile(N, heads * 128, false);
-  if (kind == TILE_BIG4 && heads % 2 == 0)
-    launch_gemm<TileBig4>(hbuf, d, N, heads * 128, d, 1, BQKV<256>{wq, wk, wv, n_q, n_kv, head0, d},
-                          EpiQKVRope<256>{q, k, v, n_q, n_kv, head0, T_len, rope_tab, rot}, s);
-  else if (kind == TILE_BIG && heads % 2 == 0)
+  if (kind == TILE_BIG && heads % 2 == 0)
     launch_gemm<TileBig>(hbuf, d, N, heads * 128, d, 1, BQKV<256>{wq, wk, wv, n_q, n_kv, head0, d},
                          EpiQKVRope<256>{q, k, v, n_q, n_kv, head0, T_len, rope_tab, rot}, s);
   else if (kind == TILE_SMALL2)
