@@ -304,6 +304,14 @@ typedef struct {
 int kvp_debug_plan(const kvp_config* cfg, int32_t B, int32_t T, kvp_plan_region* regions, int32_t capacity,
                    int32_t* n_regions, uint64_t* total_bytes);
 
+/* Test aid.  The attention kernels of the bf16 prefill keep one softmax reference per query row,
+ * fixed by the row's first key tile, and re-reference a tile (raise the reference to the tile's
+ * maximum, rescale, recompute) only when the sum of its probabilities in a lane exceeds a guard
+ * value, 2^20 by default.  This sets the guard for the whole process (limit <= 0 restores the
+ * default); a tiny value sends every tile through the re-referencing path, which tests use to
+ * check that path against the oracle.  Results are correct for any positive value. */
+void kvp_debug_flash_guard(float limit);
+
 /* Achievable-peak probes (measurement aids, not part of the path): plain kernels of known work
  * whose rate is what this chip sustains on the two roofs the path's kernels are priced against.
  * Both only enqueue one kernel on hip_stream; the caller times it (HIP events on that stream).

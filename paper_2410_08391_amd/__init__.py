@@ -10,5 +10,5 @@ from .binding import (KVP, KVPError, lib, library_path, kvp_load_weights, kvp_wo
                       kvp_prefill_predict, kvp_run_stages, kvp_free, kvp_last_error, kvp_version,
                       kvp_reference_workspace_bytes, kvp_reference_prefill, MODEL_BASE, MODEL_AUX,
                       kvp_generation_workspace_bytes, kvp_generation_step, kvp_generation_step_static,
-                      kvp_static_scratch_bytes, kvp_check_flags, kvp_debug_plan, kvp_probe_mfma, kvp_probe_stream, FLAG_TOKEN_CLAMPED, EXPORTS,
+                      kvp_static_scratch_bytes, kvp_check_flags, kvp_debug_plan, kvp_probe_mfma, kvp_probe_stream, kvp_debug_flash_guard, FLAG_TOKEN_CLAMPED, EXPORTS,
                       STAGE_AUX, STAGE_PREDICT, STAGE_BASE, STAGE_ALL, STAGE_BASE_ABSORBED, KERNEL_CLASSES)

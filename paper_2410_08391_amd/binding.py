@@ -20,7 +20,7 @@ MODEL_BASE, MODEL_AUX = 0, 1
 EXPORTS = ("kvp_load_weights", "kvp_workspace_bytes", "kvp_prefill_predict", "kvp_run_stages",
            "kvp_aux_cache_offsets", "kvp_reference_workspace_bytes", "kvp_reference_prefill",
            "kvp_generation_workspace_bytes", "kvp_generation_step", "kvp_generation_step_static", "kvp_static_scratch_bytes",
-           "kvp_check_flags", "kvp_debug_plan", "kvp_probe_mfma", "kvp_probe_stream", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
+           "kvp_check_flags", "kvp_debug_plan", "kvp_probe_mfma", "kvp_probe_stream", "kvp_debug_flash_guard", "kvp_profile_enable", "kvp_profile_reset", "kvp_profile_read",
            "kvp_free", "kvp_last_error", "kvp_version")
 FLAG_TOKEN_CLAMPED = 1
 
@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
     L.kvp_debug_plan.argtypes = [C.POINTER(Config), C.c_int32, C.c_int32, C.POINTER(PlanRegion), C.c_int32,
                                  C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
     L.kvp_debug_plan.restype = C.c_int
+    L.kvp_debug_flash_guard.argtypes = [C.c_float]
+    L.kvp_debug_flash_guard.restype = None
     L.kvp_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
     L.kvp_probe_mfma.restype = C.c_int
     L.kvp_probe_stream.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -275,6 +277,11 @@ def kvp_check_flags(handle: int, clear: bool = False) -> int:
     v = C.c_uint32()
     _check(lib().kvp_check_flags(handle, C.byref(v), 1 if clear else 0))
     return int(v.value)
+
+
+def kvp_debug_flash_guard(limit: float) -> None:
+    """Sets the overflow guard of the attention kernels' fixed-reference softmax for the process (<= 0: default)."""
+    lib().kvp_debug_flash_guard(limit)
 
 
 def kvp_probe_mfma(sink, iters: int, stream: int = 0) -> float:

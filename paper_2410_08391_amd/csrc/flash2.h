@@ -13,10 +13,11 @@
 //        MFMA:  PV(j-1), then QK(j+1)          VALU:  SM(j)
 //
 // written as 32 chunks of one MFMA, the LDS read of a later chunk's fragment and a slice of the
-// softmax, pinned by a scheduling barrier after every chunk.  The row maximum is searched beside
-// PV(j-1); the (rare) rescale of the output accumulators follows once PV(j-1) is complete, as in
-// the unpipelined order; the exponentials run beside QK(j+1).  Scores are double buffered by
-// tile parity.
+// softmax, pinned by a scheduling barrier after every chunk.  The exponentials run beside QK(j+1).
+// The softmax reference of a query row is fixed by its first key tile and only an overflow guard
+// watches the later ones (see flash_prefill_kernel: no row maximum in the steady state; the rare
+// recomputation of a tile follows once PV(j-1) and the tile's exponentials are complete).  Scores are
+// double buffered by tile parity.
 //
 // K and V tiles travel global -> LDS directly into two rings of four 16 KB slots.  At the top of
 // phase j, after the barrier, the block requests K(j+3) and V(j+2): keys are needed one phase
@@ -38,7 +39,8 @@ __global__ __launch_bounds__(F2_WAVES * 64) void flash_prefill2_kernel(const bf1
                                                                         const bf16* __restrict__ k,
                                                                         const bf16* __restrict__ vT,
                                                                         bf16* __restrict__ out, int T_len, int T_pad,
-                                                                        int n_q, int n_kv, int G, int SUBS, float c_log2) {
+                                                                        int n_q, int n_kv, int G, int SUBS, float c_log2,
+                                                                        float guard) {
   __shared__ __attribute__((aligned(1024))) bf16 kring[F2_SLOTS * FA_KT * 128];   // 64 KB
   __shared__ __attribute__((aligned(1024))) bf16 vring[F2_SLOTS * FA_KT * 128];   // 64 KB
 
@@ -133,9 +135,11 @@ __global__ __launch_bounds__(F2_WAVES * 64) void flash_prefill2_kernel(const bf1
   auto ld_v = [&](uint32_t off) { return *reinterpret_cast<const bf16x8*>(reinterpret_cast<const char*>(vring) + off); };
 
   // One phase on tile j of parity C:  MFMA PV(j-1) [PV], MFMA QK(j+1) [QK], VALU SM(j) [SM, MASK].
-  auto phase = [&](auto PVc, auto QKc, auto SMc, auto MASKc, auto Cc, int j) {
+  // FIRST: tile 0, whose row maximum becomes the reference of the row's exponentials.
+  auto phase = [&](auto PVc, auto QKc, auto SMc, auto MASKc, auto FIRSTc, auto Cc, int j) {
     constexpr bool PV = decltype(PVc)::value, QK = decltype(QKc)::value, SM = decltype(SMc)::value;
-    constexpr bool MASK = decltype(MASKc)::value;
+    constexpr bool MASK = decltype(MASKc)::value, FIRST = decltype(FIRSTc)::value;
+    static_assert(!FIRST || !PV, "the first tile has no predecessor");
     constexpr int C = decltype(Cc)::value;                   // parity of j: S(j) is sacc[C], S(j+1) goes to sacc[1-C]
     constexpr int NPV = PV ? 16 : 0, NM = NPV + (QK ? 16 : 0);
     constexpr int D = 3, R = 4;                               // fragment prefetch distance, ring size (deeper: spills, slower)
@@ -168,22 +172,26 @@ __global__ __launch_bounds__(F2_WAVES * 64) void flash_prefill2_kernel(const bf1
         }
       }
     };
-    // Vector slices.  First part (chunks 0 .. NPV-1, or before any chunk when there is no PV):
-    // mask, row maximum, exchange with the partner lane.  Second part: 16 pairs of exponentials
-    // spread over the QK chunks (or after the chunks when there is no QK).
-    float mx = -INFINITY, mx_other = 0.f, mc = 0.f, psum = 0.f;
-    auto max_slice = [&](auto E0, auto E1) {
-      constexpr int e0 = decltype(E0)::value, e1 = decltype(E1)::value;
+    // Vector work: the causal mask (last tile only), then 16 pairs of exponentials spread over the QK
+    // chunks (or after the chunks when there is no QK).  The first tile also searches its row maximum,
+    // up front (it has no PV chain to hide behind), which becomes the row's reference.
+    float mx = -INFINITY, mc = m_run * c_log2, psum = 0.f;
+    auto mask_tile = [&]() {
+      if constexpr (MASK) {
 #pragma unroll
-      for (int e = e0; e < e1; ++e) {
-        const int kt = e / 16, i = e % 16;
-        if constexpr (MASK) {
+        for (int e = 0; e < 32; ++e) {
+          const int kt = e / 16, i = e % 16;
           // accumulator element i of key tile kt is key kv0 + 32 kt + 16 (i/8) + 8 g + i%8
           int key = kv0 + 32 * kt + 16 * (i / 8) + 8 * g + (i % 8);
           if (key > qpos) sacc[C][kt][i] = -INFINITY;
         }
-        mx = fmaxf(mx, sacc[C][kt][i]);
       }
+    };
+    auto row_max = [&]() {                                    // this lane's 32 scores, then the partner lane's
+      mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 32; ++e) mx = fmaxf(mx, sacc[C][e / 16][e % 16]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     };
     auto exp_pair = [&](auto Uc) {
       constexpr int u = decltype(Uc)::value;
@@ -195,16 +203,27 @@ __global__ __launch_bounds__(F2_WAVES * 64) void flash_prefill2_kernel(const bf1
       pf[kt * 2 + sgrp][e0] = (bf16)p0;
       pf[kt * 2 + sgrp][e0 + 1] = (bf16)p1;
     };
+    auto all_exps = [&]() {
+      auto run = [&](auto self, auto Uc) -> void {
+        exp_pair(Uc);
+        if constexpr (decltype(Uc)::value + 1 < 16) self(self, std::integral_constant<int, decltype(Uc)::value + 1>{});
+      };
+      run(run, std::integral_constant<int, 0>{});
+    };
+    // new reference m_new >= m_run for the row: what has been accumulated so far is rescaled to it
+    auto move_reference = [&](float m_new) {
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);   // m_run = -inf (first tile): 0 * 0
+      l_run *= alpha;
+      m_run = m_new;
+      mc = m_run * c_log2;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc_o[dt][i] *= alpha;
+    };
     auto valu = [&](auto Mc) {
       constexpr int M = decltype(Mc)::value;
-      if constexpr (SM) {
-        if constexpr (M < NPV) {
-          if constexpr (M < 12) max_slice(std::integral_constant<int, (32 * M) / 12>{}, std::integral_constant<int, (32 * (M + 1)) / 12>{});
-          else if constexpr (M == 12) mx_other = __shfl_xor(mx, 32, 64);
-        } else if constexpr (QK) {
-          exp_pair(std::integral_constant<int, M - NPV>{});
-        }
-      }
+      if constexpr (SM && QK && M >= NPV) exp_pair(std::integral_constant<int, M - NPV>{});
     };
     auto chunk = [&](auto Mc) {
       constexpr int M = decltype(Mc)::value;
@@ -231,35 +250,24 @@ __global__ __launch_bounds__(F2_WAVES * 64) void flash_prefill2_kernel(const bf1
       };
       run(run, std::integral_constant<int, 0>{});
     }
-    if constexpr (SM && !PV) {                                // no chain to hide behind: search the maximum up front
-      max_slice(std::integral_constant<int, 0>{}, std::integral_constant<int, 32>{});
-      mx_other = __shfl_xor(mx, 32, 64);
+    if constexpr (SM) mask_tile();
+    if constexpr (SM && FIRST) {                              // tile 0: its row maximum is the reference from here on
+      row_max();
+      move_reference(mx);
     }
     chunks(std::integral_constant<int, 0>{}, std::integral_constant<int, NPV>{});
-    if constexpr (SM) {
-      mx = fmaxf(mx, mx_other);
-      // lazy running maximum, compared in the exp2 domain (see flash_prefill_kernel)
-      const bool move = mx * c_log2 > m_run * c_log2 + 8.f || m_run == -INFINITY;
-      if (__builtin_amdgcn_ballot_w64(move) != 0) {   // wave-uniform, rare after the first tiles
-        const float m_new = move ? mx : m_run;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
-        l_run *= alpha;
-        m_run = m_new;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc_o[dt][i] *= alpha;
-      }
-      mc = m_run * c_log2;
-    }
     chunks(std::integral_constant<int, NPV>{}, std::integral_constant<int, NM>{});
     if constexpr (SM) {
-      if constexpr (!QK) {
-        auto run = [&](auto self, auto Uc) -> void {
-          exp_pair(Uc);
-          if constexpr (decltype(Uc)::value + 1 < 16) self(self, std::integral_constant<int, decltype(Uc)::value + 1>{});
-        };
-        run(run, std::integral_constant<int, 0>{});
+      if constexpr (!QK) all_exps();
+      if constexpr (!FIRST) {
+        // Overflow guard (see flash_prefill_kernel).  PV(j-1) is complete here, so what has been accumulated
+        // may be rescaled; the tile's probabilities are recomputed against the raised reference.
+        if (__builtin_amdgcn_ballot_w64(!(psum <= guard)) != 0) {   // wave-uniform, rare
+          row_max();
+          move_reference(fmaxf(m_run, mx));
+          psum = 0.f;
+          all_exps();
+        }
       }
       l_run += psum;
     }
@@ -288,35 +296,35 @@ __global__ __launch_bounds__(F2_WAVES * 64) void flash_prefill2_kernel(const bf1
   }
   {
     // QK(0) alone: expressed as the QK part of a phase "-1" (K(j+1) with j = -1, parity 1 -> sacc[0])
-    phase(F_{}, T_{}, F_{}, F_{}, C1{}, -1);
+    phase(F_{}, T_{}, F_{}, F_{}, F_{}, C1{}, -1);
   }
   // ---- phase 0: QK(1) beside SM(0) ----
   top(0);
-  if (n_tiles == 1) phase(F_{}, F_{}, T_{}, T_{}, C0{}, 0);
-  else phase(F_{}, T_{}, T_{}, F_{}, C0{}, 0);
+  if (n_tiles == 1) phase(F_{}, F_{}, T_{}, T_{}, T_{}, C0{}, 0);
+  else phase(F_{}, T_{}, T_{}, F_{}, T_{}, C0{}, 0);
   // ---- phases 1 .. n-2: PV(j-1), QK(j+1) beside SM(j), unmasked ----
   int j = 1;
   for (; j + 2 < n_tiles; j += 2) {
     top(j);
-    phase(T_{}, T_{}, T_{}, F_{}, C1{}, j);
+    phase(T_{}, T_{}, T_{}, F_{}, F_{}, C1{}, j);
     top(j + 1);
-    phase(T_{}, T_{}, T_{}, F_{}, C0{}, j + 1);
+    phase(T_{}, T_{}, T_{}, F_{}, F_{}, C0{}, j + 1);
   }
   if (j + 1 < n_tiles) {                               // one more unmasked phase (odd j)
     top(j);
-    phase(T_{}, T_{}, T_{}, F_{}, C1{}, j);
+    phase(T_{}, T_{}, T_{}, F_{}, F_{}, C1{}, j);
     ++j;
   }
   // ---- phase n-1 (if n > 1): PV(n-2) beside the masked SM(n-1) ----
   if (n_tiles > 1) {
     top(j);
-    if (j & 1) phase(T_{}, F_{}, T_{}, T_{}, C1{}, j);
-    else phase(T_{}, F_{}, T_{}, T_{}, C0{}, j);
+    if (j & 1) phase(T_{}, F_{}, T_{}, T_{}, F_{}, C1{}, j);
+    else phase(T_{}, F_{}, T_{}, T_{}, F_{}, C0{}, j);
     ++j;
   }
   // ---- phase n: PV(n-1) ----
   top(j);
-  phase(T_{}, F_{}, F_{}, F_{}, C0{}, j);
+  phase(T_{}, F_{}, F_{}, F_{}, F_{}, C0{}, j);
   __builtin_amdgcn_s_waitcnt(0x0F70);     // drain the clamped tail requests before the block ends
 
   // O^T accumulator element i of dim tile dt: dim 32 dt + 8 (i/4) + 4 g + i%4, query column l32

@@ -1168,6 +1168,8 @@ int kvp_generation_step_static(kvp_handle* h, const int32_t* tokens, int32_t B, 
                          "static scratch", hip_stream);
 }
 
+void kvp_debug_flash_guard(float limit) { mfma_set_flash_guard(limit); }
+
 int kvp_profile_enable(kvp_handle* h, int32_t on) {
   if (!h) return fail(KVP_ERR_NULL, "handle is NULL");
   h->prof_on = on != 0;

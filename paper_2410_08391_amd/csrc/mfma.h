@@ -39,6 +39,8 @@ void mfma_qkv_rope(const bf16* hbuf, const bf16* wq, const bf16* wk, const bf16*
 // causal grouped-query flash attention (head_dim 128): q, k token-major, v from the transposed copy
 void mfma_flash_prefill(const bf16* q, const bf16* k, const bf16* vT, bf16* out, int B, int T_len, int n_q, int n_kv,
                         hipStream_t s);
+// overflow guard of the attention kernels' fixed-reference softmax, for the whole process (0: the default)
+void mfma_set_flash_guard(float limit);
 // X[M,N] += A[M,K] W[N,K]^T  (float32 residual stream)
 void mfma_gemm_residual(const bf16* A, const bf16* W, float* X, int M, int N, int K, hipStream_t s);
 // act[M,F] = silu(A Wg^T) * (A Wu^T)

@@ -259,6 +259,65 @@ def test_pipelined_flash_attention_matches_unpipelined_bitwise(monkeypatch, grou
         np.testing.assert_array_equal(a[k], b[k])
 
 
+@pytest.mark.parametrize("group,seq_len", [(4, 449), (8, 200), (3, 330), (2, 200), (1, 150)])
+@pytest.mark.parametrize("guard", [1e-30, 0.9])
+def test_flash_attention_rereferencing_path(monkeypatch, group, seq_len, guard):
+    """The attention kernels fix a row's softmax reference at its first key tile and re-reference a tile
+    (raise the reference to the tile's maximum, rescale what is accumulated, recompute the tile) only when
+    an overflow guard trips.  With the guard forced below any sum of probabilities EVERY later tile takes
+    that path (1e-30), or the tiles whose scores exceed the reference do (0.9: a lane's 32 probabilities sum
+    to more than 0.9 only with scores near or above it): the results must still match the oracle, and the
+    pipelined and the plain kernel (groups 1 and 2 only have the plain one) must still agree bit for bit."""
+    import paper_2410_08391_amd as K
+    aux_d = 128 * group // 4 if group == 4 else 256
+    cfg = S.tiny_config("bf16", base=(3, 256, 4, 2, 128, 320), aux=(3, aux_d, group, 1, 128, 192),
+                        batch=2, seq_len=seq_len, vocab=211, seed=59 + seq_len)
+    store = S.WeightStore(cfg)
+    tok = S.draw_tokens(cfg)
+    ref = O.kvp_prefill_predict(cfg, store.f64, tok)
+    K.kvp_debug_flash_guard(guard)
+    try:
+        a = run_gpu(cfg, store, tok)
+        compare(cfg, a, ref)
+        if group >= 3:
+            monkeypatch.setenv("KVP_FLASH_V1", "1")
+            b = run_gpu(cfg, store, tok)
+            for k in ("K_hat", "V_hat", "logits", "first"):
+                np.testing.assert_array_equal(a[k], b[k])
+    finally:
+        K.kvp_debug_flash_guard(0.0)
+
+
+def test_flash_attention_scores_far_above_the_first_tile(monkeypatch):
+    """Queries and keys scaled up so that later key tiles score tens of units (in the exponent) above the
+    first one: the default guard (2^20) trips on real overflow-bound data.  Outputs stay finite, the two
+    kernels agree bit for bit, and the result matches the forced re-referencing of every tile (which is the
+    ordinary running-maximum softmax) to rounding."""
+    import torch
+    import paper_2410_08391_amd as K
+    cfg = S.tiny_config("bf16", base=(2, 256, 4, 2, 128, 320), aux=(2, 512, 4, 1, 128, 192), batch=2, seq_len=700, vocab=211, seed=67)
+    base = S.WeightStore(cfg)
+    big = {n: base.get(n) * (24.0 if n.endswith(("L0.wq", "L0.wk")) and n.startswith("aux.") else 1.0) for n in S.hot_path_tensor_names(cfg)}
+    store = S.WeightStore(cfg, overrides=big)
+    tok = S.draw_tokens(cfg)
+    a = run_gpu(cfg, store, tok)
+    assert np.isfinite(a["K_A"]).all() and np.isfinite(a["V_A"]).all() and np.isfinite(a["logits"]).all()
+    monkeypatch.setenv("KVP_FLASH_V1", "1")
+    b = run_gpu(cfg, store, tok)
+    np.testing.assert_array_equal(a["K_A"], b["K_A"])
+    np.testing.assert_array_equal(a["V_A"], b["V_A"])
+    monkeypatch.delenv("KVP_FLASH_V1")
+    K.kvp_debug_flash_guard(1e-30)
+    try:
+        c = run_gpu(cfg, store, tok)
+    finally:
+        K.kvp_debug_flash_guard(0.0)
+    # layer 1's keys / values see layer 0's attention output: same mathematics, another reference per tile
+    for name in ("K_A", "V_A"):
+        err = np.abs(a[name][1].astype(np.float64) - c[name][1]).max() / np.abs(c[name][1]).max()
+        assert err <= 1e-2, f"{name}: fixed reference against per-tile maximum differ by {err:.3e}"
+
+
 @pytest.mark.parametrize("keep", [0.5, 0.25])
 def test_layer_pruned_auxiliary_model_square_predictor(keep):
     """KVP-LP shape (Sec. 4.2 "Architectural Details": the auxiliary network is a layer-pruned copy of the
