@@ -319,8 +319,9 @@ void kvp_debug_flash_guard(float limit);
  *   kernels here use (v_mfma_f32_32x32x16_bf16), no memory traffic; *flops_out (host) receives the
  *   floating-point operations the launch performs; sink: device, >= 4 bytes, never written in
  *   practice.
- * kvp_probe_stream: kind 0 reads `bytes` from src, 1 copies src -> dst, 2 fills dst; src / dst
- *   device, 16-byte aligned, `bytes` long (kind 0 writes nothing but needs dst != NULL).
+ * kvp_probe_stream: kind 0 reads `bytes` from src (contiguous share per block, non-temporal loads:
+ *   the fastest way found to stream from memory on this chip), 1 copies src -> dst, 2 fills dst;
+ *   src / dst device, 16-byte aligned, `bytes` long (kind 0 writes nothing but needs dst != NULL).
  * Errors: KVP_ERR_NULL, KVP_ERR_BAD_SHAPE, KVP_ERR_HIP (kvp_last_error is not set). */
 int kvp_probe_mfma(float* sink, int32_t iters, double* flops_out, void* hip_stream);
 int kvp_probe_stream(int32_t kind, const void* src, void* dst, size_t bytes, void* hip_stream);

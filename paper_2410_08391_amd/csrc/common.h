@@ -49,6 +49,14 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// 16-byte load of data that is read once per call (weights of a one-token step, the predicted cache): the
+// non-temporal hint keeps the line from displacing reused data in L2 and the memory-side cache, and the chip
+// streams such reads measurably faster than plain loads.
+__device__ __forceinline__ bf16x8 load_stream8(const bf16* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p)));
+}
+
 // Loads 8 consecutive elements as floats (16-byte load for bf16, two for float).
 __device__ __forceinline__ void load8(const bf16* p, float (&out)[8]) {
   bf16x8 v = *reinterpret_cast<const bf16x8*>(p);

@@ -221,16 +221,16 @@ __global__ __launch_bounds__(NW * 64) void gemv_chain_kernel(ChainArgs a) {
         const size_t off = (size_t)(u % 4) * 4 * K + (size_t)(sb + u / 4 * 4) * 32;
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          wv[t * NM][u] = *reinterpret_cast<const bf16x8*>(ok ? wrow[t] + off : a.W);
-          if (MODE == 2) wv[t * NM + NM - 1][u] = *reinterpret_cast<const bf16x8*>(ok ? w2row[t] + off : a.W2);
+          wv[t * NM][u] = load_stream8(ok ? wrow[t] + off : a.W);
+          if (MODE == 2) wv[t * NM + NM - 1][u] = load_stream8(ok ? w2row[t] + off : a.W2);
         }
       } else {
         const int k = (sb + u) * 32 + g * 8;
         const bool ok = (sb + u < s1) && (k < K);
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          wv[t * NM][u] = *reinterpret_cast<const bf16x8*>(ok ? wrow[t] + k : a.W);
-          if (MODE == 2) wv[t * NM + NM - 1][u] = *reinterpret_cast<const bf16x8*>(ok ? w2row[t] + k : a.W2);
+          wv[t * NM][u] = load_stream8(ok ? wrow[t] + k : a.W);
+          if (MODE == 2) wv[t * NM + NM - 1][u] = load_stream8(ok ? w2row[t] + k : a.W2);
         }
       }
     }
@@ -390,8 +390,8 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(ChainArgs a) {
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         const size_t off = (size_t)min(row0 + r, N - 1) * K + (ok ? k : 0);
-        wv[0][r][c] = *reinterpret_cast<const bf16x8*>(a.W + off);
-        if (MODE == 2) wv[NM - 1][r][c] = *reinterpret_cast<const bf16x8*>(a.W2 + off);
+        wv[0][r][c] = load_stream8(a.W + off);
+        if (MODE == 2) wv[NM - 1][r][c] = load_stream8(a.W2 + off);
       }
     }
   };

@@ -469,13 +469,13 @@ __global__ __launch_bounds__(256) void decode_attn_mfma_kernel(const float* __re
     for (int t = 0; t < 2; ++t) {
       const bf16* row = kbase + (size_t)min(k0 + 16 * t + r, last_row) * HD + g * 8;
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) kreg[t][s4] = *reinterpret_cast<const bf16x8*>(row + 32 * s4);
+      for (int s4 = 0; s4 < 4; ++s4) kreg[t][s4] = load_stream8(row + 32 * s4);
     }
   };
   auto issue_v = [&](int k0) {                    // rows k0 + 4 j + rgrp, dims 8 sub
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      vreg[j] = *reinterpret_cast<const bf16x8*>(vbase + (size_t)min(k0 + 4 * j + rgrp, last_row) * HD + sub * 8);
+      vreg[j] = load_stream8(vbase + (size_t)min(k0 + 4 * j + rgrp, last_row) * HD + sub * 8);
   };
   const int k_first = c0 + wave * KPI;
   if (k_first < c1) { issue_k(k_first); issue_v(k_first); }

@@ -52,7 +52,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void store16(bf16* dst, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(dst), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(dst), "v"(v) : "memory");
 }
 
 constexpr int wait_imm(int x) { return (x & 15) | ((x >> 4) << 14) | 0x0070; }   // vmcnt(x), lgkmcnt(0)
