@@ -93,9 +93,9 @@ struct ChainArgs {
 };
 
 // Steps per batch of loads: as many as keep weights (4 registers per step and row tile) plus
-// right-hand sides (8 per group of QG steps) within a budget out of the 128 registers a wave of
-// a 16-wave block may hold (84, or 64 where the LDS route needs temporaries), at most 16 and at
-// least one unit.
+// right-hand sides (8 per group of QG steps) within a budget out of the 128 registers a wave may
+// hold when two 8-wave blocks share a CU (84, or 64 where the LDS route needs temporaries), at
+// most 16 and at least one unit.
 constexpr int chain_batch_steps(int rtnm, int qg, int unit, int budget) {
   int u = unit;                                // unit: a multiple of qg
   while (u + unit <= 16 && rtnm * (u + unit) * 4 + ((u + unit) / qg) * 8 <= budget) u += unit;
@@ -128,6 +128,10 @@ __device__ __forceinline__ bf16x8 row_shift_down(bf16x8 v) {
 // stored at position piece ^ row, which keeps both the writes and the reads free of bank
 // conflicts).  No barrier is involved: the region is private to the wave and LDS operations of
 // a wave execute in order.  Needs K % 128 == 0 and N % 16 == 0.
+//
+// NW: waves per block, which split K among them.  The launcher uses 8: two such blocks fit a CU
+// (registers and LDS), so one block's loads are in flight while the other reduces, stores and
+// retires; 16-wave blocks, one per CU, streamed the weights 8-15 % slower, 4-wave blocks 4 % slower.
 template <int MODE, bool NORM, int NW, int RT, int QG, bool LDSW = false>
 __global__ __launch_bounds__(NW * 64) void gemv_chain_kernel(ChainArgs a) {
   // More than 16 right-hand sides: grid row y serves right-hand sides 16 y .. 16 y + 15.  The rows
@@ -617,22 +621,24 @@ static bool chain_direct_loads() {
   return v;
 }
 
-template <int MODE, bool NORM, int NW, int QG>
+constexpr int CHAIN_NW = 8;                    // waves per block of gemv_chain_kernel
+
+template <int MODE, bool NORM, int QG>
 static void launch_chain_qg(const ChainArgs& a, int rt, hipStream_t s) {
   // row tiles per block are capped so that weights and right-hand sides of a batch fit the registers
   constexpr int RT_MAX = (QG == 4 ? 4 : 2) / (MODE == 2 ? 2 : 1);
+  constexpr int NW = CHAIN_NW;
   dim3 block(NW * 64);
   int tiles = (a.N + 15) / 16;
   const unsigned gy = (unsigned)((a.B + 15) / 16);     // groups of 16 right-hand sides
   if (rt > RT_MAX) rt = RT_MAX;
-  if constexpr (NW == 16) {
-    if (a.K % 128 == 0 && a.N % 16 == 0 && !chain_direct_loads()) {      // coalesced weights through LDS (at most 2 tiles x matrices)
-      if constexpr (RT_MAX >= 2 && MODE != 2) {
-        if (rt >= 2) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 2, QG, true>), dim3((tiles + 1) / 2, gy), block, 0, s, a); return; }
-      }
-      hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG, true>), dim3(tiles, gy), block, 0, s, a);
-      return;
+  // rows of 2048 and more elements: coalesced weights through LDS (at most 2 tiles x matrices)
+  if (a.K >= 2048 && a.K % 128 == 0 && a.N % 16 == 0 && !chain_direct_loads()) {
+    if constexpr (RT_MAX >= 2 && MODE != 2) {
+      if (rt >= 2) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 2, QG, true>), dim3((tiles + 1) / 2, gy), block, 0, s, a); return; }
     }
+    hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG, true>), dim3(tiles, gy), block, 0, s, a);
+    return;
   }
   if constexpr (RT_MAX >= 4) {
     if (rt == 4) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 4, QG>), dim3((tiles + 3) / 4, gy), block, 0, s, a); return; }
@@ -642,14 +648,14 @@ static void launch_chain_qg(const ChainArgs& a, int rt, hipStream_t s) {
   }
   hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG>), dim3(tiles, gy), block, 0, s, a);
 }
-template <int MODE, bool NORM, int NW>
+template <int MODE, bool NORM>
 static void launch_chain_rt(const ChainArgs& a, int rt, hipStream_t s) {
-  if (a.B <= 4) launch_chain_qg<MODE, NORM, NW, 4>(a, rt, s);
-  else if (a.B <= 8) launch_chain_qg<MODE, NORM, NW, 2>(a, rt, s);
-  else launch_chain_qg<MODE, NORM, NW, 1>(a, rt, s);
+  if (a.B <= 4) launch_chain_qg<MODE, NORM, 4>(a, rt, s);
+  else if (a.B <= 8) launch_chain_qg<MODE, NORM, 2>(a, rt, s);
+  else launch_chain_qg<MODE, NORM, 1>(a, rt, s);
 }
 
-// Row tiles per block: as few as keep the whole grid resident at once (256 CUs, one block each).
+// Row tiles per block: more of them for the tall matrices (the LM head), whose grids are many times the chip.
 int chain_row_tiles(int N) {
   int tiles = (N + 15) / 16;
   if (tiles <= 256) return 1;
@@ -664,10 +670,7 @@ int chain_ssq_parts(int N, int B) {
 template <int MODE, bool NORM>
 static void launch_chain(ChainArgs a, hipStream_t s) {
   if (a.B <= 2) { launch_rows<MODE, NORM>(a, s); return; }
-  int rt = chain_row_tiles(a.N);
-  int steps = (a.K + 31) / 32;
-  if (steps >= 64) launch_chain_rt<MODE, NORM, 16>(a, rt, s);
-  else launch_chain_rt<MODE, NORM, 8>(a, rt, s);
+  launch_chain_rt<MODE, NORM>(a, chain_row_tiles(a.N), s);
 }
 
 void launch_base_embed(const int32_t* tokens, int T_len, const bf16* E, int vocab, const bf16* gain, float* y, bf16* uh,
