@@ -657,9 +657,17 @@ static bool launch_decode_hd(int G, dim3 grid, hipStream_t s, const float* q, co
 
 int decode_attn_splits(int B, int n_kv, int T_len) {
   // about two blocks per CU (measured best on the four benchmark shapes), at least 64 keys per block
-  int want = (512 + B * n_kv - 1) / (B * n_kv);
+  const int pairs = B * n_kv;
+  int want = (512 + pairs - 1) / pairs;
   int max_by_len = (T_len + 63) / 64;
   int n = want < max_by_len ? want : max_by_len;
+  // ... and blocks of 256 keys rather than shorter ones (a wave then runs two iterations and more, not one),
+  // as long as that still leaves a block for every CU
+  const int long_chunks = (T_len + 255) / 256, one_per_cu = (256 + pairs - 1) / pairs;
+  if (n > long_chunks) {
+    const int floor_n = n < one_per_cu ? n : one_per_cu;
+    n = long_chunks > floor_n ? long_chunks : floor_n;
+  }
   // one or two sequences: the output projection merges the partials in its prologue (one launch
   // fewer per layer on a latency-bound chain); keep that merge to one batch of eight
   if (B <= 2 && n > 8) n = 8;
