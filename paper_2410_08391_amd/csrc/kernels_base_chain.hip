@@ -132,7 +132,10 @@ __device__ __forceinline__ bf16x8 row_shift_down(bf16x8 v) {
 // NW: waves per block, which split K among them.  The launcher uses 8: two such blocks fit a CU
 // (registers and LDS), so one block's loads are in flight while the other reduces, stores and
 // retires; 16-wave blocks, one per CU, streamed the weights 8-15 % slower, 4-wave blocks 4 % slower.
-template <int MODE, bool NORM, int NW, int RT, int QG, bool LDSW = false>
+//
+// STREAM: the weights are loaded with the non-temporal hint (read once per launch).  Off for more than 16
+// right-hand sides, where the grid's rows share each weight tile through L2 and the hint costs 10 %.
+template <int MODE, bool NORM, int NW, int RT, int QG, bool LDSW = false, bool STREAM = true>
 __global__ __launch_bounds__(NW * 64) void gemv_chain_kernel(ChainArgs a) {
   // More than 16 right-hand sides: grid row y serves right-hand sides 16 y .. 16 y + 15.  The rows
   // of the grid run side by side, so a weight tile fetched for one of them is in L2 for the
@@ -206,6 +209,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_chain_kernel(ChainArgs a) {
   const bf16* xh = a.xh + (size_t)n * K;
   const bf16* xl = a.xl + (size_t)n * K;
 
+  auto load_w = [](const bf16* p) { return STREAM ? load_stream8(p) : *reinterpret_cast<const bf16x8*>(p); };
   f32x4 acc[RT * NM];
 #pragma unroll
   for (int m = 0; m < RT * NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -225,16 +229,16 @@ __global__ __launch_bounds__(NW * 64) void gemv_chain_kernel(ChainArgs a) {
         const size_t off = (size_t)(u % 4) * 4 * K + (size_t)(sb + u / 4 * 4) * 32;
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          wv[t * NM][u] = load_stream8(ok ? wrow[t] + off : a.W);
-          if (MODE == 2) wv[t * NM + NM - 1][u] = load_stream8(ok ? w2row[t] + off : a.W2);
+          wv[t * NM][u] = load_w(ok ? wrow[t] + off : a.W);
+          if (MODE == 2) wv[t * NM + NM - 1][u] = load_w(ok ? w2row[t] + off : a.W2);
         }
       } else {
         const int k = (sb + u) * 32 + g * 8;
         const bool ok = (sb + u < s1) && (k < K);
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          wv[t * NM][u] = load_stream8(ok ? wrow[t] + k : a.W);
-          if (MODE == 2) wv[t * NM + NM - 1][u] = load_stream8(ok ? w2row[t] + k : a.W2);
+          wv[t * NM][u] = load_w(ok ? wrow[t] + k : a.W);
+          if (MODE == 2) wv[t * NM + NM - 1][u] = load_w(ok ? w2row[t] + k : a.W2);
         }
       }
     }
@@ -623,7 +627,7 @@ static bool chain_direct_loads() {
 
 constexpr int CHAIN_NW = 8;                    // waves per block of gemv_chain_kernel
 
-template <int MODE, bool NORM, int QG>
+template <int MODE, bool NORM, int QG, bool STREAM = true>
 static void launch_chain_qg(const ChainArgs& a, int rt, hipStream_t s) {
   // row tiles per block are capped so that weights and right-hand sides of a batch fit the registers
   constexpr int RT_MAX = (QG == 4 ? 4 : 2) / (MODE == 2 ? 2 : 1);
@@ -635,24 +639,25 @@ static void launch_chain_qg(const ChainArgs& a, int rt, hipStream_t s) {
   // rows of 2048 and more elements: coalesced weights through LDS (at most 2 tiles x matrices)
   if (a.K >= 2048 && a.K % 128 == 0 && a.N % 16 == 0 && !chain_direct_loads()) {
     if constexpr (RT_MAX >= 2 && MODE != 2) {
-      if (rt >= 2) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 2, QG, true>), dim3((tiles + 1) / 2, gy), block, 0, s, a); return; }
+      if (rt >= 2) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 2, QG, true, STREAM>), dim3((tiles + 1) / 2, gy), block, 0, s, a); return; }
     }
-    hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG, true>), dim3(tiles, gy), block, 0, s, a);
+    hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG, true, STREAM>), dim3(tiles, gy), block, 0, s, a);
     return;
   }
   if constexpr (RT_MAX >= 4) {
-    if (rt == 4) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 4, QG>), dim3((tiles + 3) / 4, gy), block, 0, s, a); return; }
+    if (rt == 4) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 4, QG, false, STREAM>), dim3((tiles + 3) / 4, gy), block, 0, s, a); return; }
   }
   if constexpr (RT_MAX >= 2) {
-    if (rt >= 2) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 2, QG>), dim3((tiles + 1) / 2, gy), block, 0, s, a); return; }
+    if (rt >= 2) { hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 2, QG, false, STREAM>), dim3((tiles + 1) / 2, gy), block, 0, s, a); return; }
   }
-  hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG>), dim3(tiles, gy), block, 0, s, a);
+  hipLaunchKernelGGL((gemv_chain_kernel<MODE, NORM, NW, 1, QG, false, STREAM>), dim3(tiles, gy), block, 0, s, a);
 }
 template <int MODE, bool NORM>
 static void launch_chain_rt(const ChainArgs& a, int rt, hipStream_t s) {
   if (a.B <= 4) launch_chain_qg<MODE, NORM, 4>(a, rt, s);
   else if (a.B <= 8) launch_chain_qg<MODE, NORM, 2>(a, rt, s);
-  else launch_chain_qg<MODE, NORM, 1>(a, rt, s);
+  else if (a.B <= 16) launch_chain_qg<MODE, NORM, 1>(a, rt, s);
+  else launch_chain_qg<MODE, NORM, 1, false>(a, rt, s);       // several grid rows share the weights through L2
 }
 
 // Row tiles per block: more of them for the tall matrices (the LM head), whose grids are many times the chip.
