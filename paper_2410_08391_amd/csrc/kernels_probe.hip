@@ -43,48 +43,36 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sin
 }
 
 // kind 0: read src;  1: copy src -> dst;  2: fill dst.  n16: number of 16-byte pieces.
-// The read is shaped the way the chip was measured to stream fastest: every block walks one contiguous share
-// with eight non-temporal 16-byte loads per thread in flight (plain loads at the same shape are ~10 % slower,
-// a grid-strided walk up to 20 %).
+// Shaped the way the chip was measured to stream fastest: every block walks one contiguous share with eight
+// 16-byte accesses per thread in flight; reads carry the non-temporal hint (plain loads at the same shape are
+// ~10 % slower, a grid-strided walk up to 20 %), the copy's stores too, the fill's stores are plain (the hint
+// costs a fill 5-10 %).
 template <int KIND>
 __global__ __launch_bounds__(256) void probe_stream_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16,
                                                            uint32_t* __restrict__ sink) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  if (KIND == 0) {
-    constexpr int U = 8;
-    const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
-    const size_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
-    const u32x4* p = reinterpret_cast<const u32x4*>(src);
-    uint32_t x = 0;
-    for (size_t i0 = lo + threadIdx.x; i0 < hi; i0 += (size_t)U * 256) {
-      u32x4 v[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const size_t i = i0 + (size_t)u * 256;
-        v[u] = __builtin_nontemporal_load(p + (i < hi ? i : i0));
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) x ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
-    }
-    if (x == 0x9e3779b9u && src[0].x == 0x7f4a7c15u) sink[0] = x;   // practically never; keeps the loads alive
-    return;
-  }
-  constexpr int U = 4;
-  const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x; i0 < n16; i0 += U * stride) {
-    uint4 v[U];
+  constexpr int U = 8;
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+  const u32x4* p = reinterpret_cast<const u32x4*>(src);
+  u32x4* q = reinterpret_cast<u32x4*>(dst);
+  uint32_t x = 0;
+  for (size_t i0 = lo + threadIdx.x; i0 < hi; i0 += (size_t)U * 256) {
+    u32x4 v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t i = i0 + u * stride;
-      if (KIND != 2) v[u] = src[i < n16 ? i : i0];
-      else v[u] = uint4{(uint32_t)i, 1u, 2u, 3u};
+      const size_t i = i0 + (size_t)u * 256;
+      if (KIND != 2) v[u] = __builtin_nontemporal_load(p + (i < hi ? i : i0));
+      else v[u] = u32x4{(uint32_t)i, 1u, 2u, 3u};
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t i = i0 + u * stride;
-      if (i < n16) dst[i] = v[u];
+      const size_t i = i0 + (size_t)u * 256;
+      if (KIND == 0) x ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+      else if (i < hi) { if (KIND == 1) __builtin_nontemporal_store(v[u], q + i); else q[i] = v[u]; }
     }
   }
+  if (KIND == 0 && x == 0x9e3779b9u && src[0].x == 0x7f4a7c15u) sink[0] = x;   // practically never; keeps the loads alive
 }
 
 }  // namespace kvp
