@@ -28,10 +28,11 @@ def test_row_kernels_wide_rows(B, d, heads, kv, ffn):
     compare(cfg, got, O.kvp_prefill_predict(cfg, store.f64, tok))
 
 
-@pytest.mark.parametrize("B", [3, 4, 7, 8, 9, 16])
+@pytest.mark.parametrize("B", [3, 4, 7, 8, 9, 16, 17, 37])
 def test_chain_kernels_coalesced_route(B):
     """K = 2048 and 2176 (>= 64 steps, multiples of 128), N = 2048 (one row tile per block) and an
-    LM head of 4112 rows (two row tiles per block)."""
+    LM head of 4112 rows (two row tiles per block).  17 and 37 sequences: grid rows of 16 right-hand
+    sides in one launch (the last row ragged), which load the weights without the non-temporal hint."""
     cfg = S.tiny_config("bf16", base=(2, 2048, 16, 4, 128, 2176), aux=AUX, batch=B, seq_len=40, vocab=4112, seed=109 + B)
     store = S.WeightStore(cfg)
     tok = S.draw_tokens(cfg)
