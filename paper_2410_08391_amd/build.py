@@ -4,7 +4,9 @@
 
 Each source is compiled to an object in parallel, then linked into
 paper_2410_08391_amd/libkvp.so.  The packed-FP32 instruction feature is
-switched off for all device code ("Build flags").
+switched off for all device code: the compiler then emits no v_pk_*_f32
+from ordinary float arithmetic, forms of which have given wrong results on
+the target machines.
 """
 from __future__ import annotations
 
