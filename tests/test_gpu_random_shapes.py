@@ -1,6 +1,7 @@
 """Seeded random small configurations (head counts, widths, layer maps, batch and prompt lengths, cache capacity,
 query / key norm, both element types and both kernel families) through the C ABI against the oracle: the whole path,
 the absorbed base step where the library serves the shape, and on a handle sized larger than the call."""
+import os
 import random
 
 import numpy as np
@@ -39,7 +40,11 @@ def _draw(rng, case):
                          qk_norm=rng.random() < 0.3)
 
 
-@pytest.mark.parametrize("case", range(16))
+# 16 cases by default; KVP_TEST_RANDOM_CASES=N draws the first N of the same seeded sequence for a longer sweep
+N_CASES = int(os.environ.get("KVP_TEST_RANDOM_CASES", "16"))
+
+
+@pytest.mark.parametrize("case", range(N_CASES))
 def test_random_configuration(case):
     import paper_2410_08391_amd as K
     rng = random.Random(4000 + case)
