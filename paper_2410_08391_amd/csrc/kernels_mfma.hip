@@ -209,8 +209,11 @@ static TileKind pick_tile(int M, int Nv, bool narrow_ok, int batches = 1) {
   // 128 x 128 tiles need two rounds of the chip's 512 slots, at a lower rate per CU, while the big tiles finish
   // in one (measured at 8192 tokens, d = 1536: O / down projections 101 -> 80 us per launch), and the CUs they
   // leave idle serve the base chain on the other stream.
-  const char* z = getenv("KVP_GEMM_ZONE");             // tuning: "0" old rule, "2" also one to one and a half rounds
-  const int zone = z ? z[0] - '0' : 1;
+  // The same holds between one and one and a half rounds (8192 tokens, 2560 virtual columns: the QKV projection of
+  // a d = 1536 model): alone the big tile is 1 % slower there, but the CUs its short second round leaves idle take
+  // the base chain's kernels, and the time to first token is 1.2 % shorter.
+  const char* z = getenv("KVP_GEMM_ZONE");             // tuning: "0" 128 x 128 tiles below 1.5 rounds, "1" big tiles up to one round only
+  const int zone = z ? z[0] - '0' : 2;
   if (zone >= 1 && big > 128 && big <= 256) return TILE_BIG;
   if (zone >= 2 && big > 256 && big < 384) return TILE_BIG;
   long small = (long)((M + 127) / 128) * ((Nv + 127) / 128);
